@@ -1,0 +1,364 @@
+// C ABI of the library (include/dualkv.h): host-side validation, workspace carving and dispatch.
+// Nothing here touches device memory except through kernel launches on the caller's stream.
+#include "../../include/dualkv.h"
+
+#include "common.h"
+#include "launch.h"
+
+namespace {
+
+using dkv::AttnParams;
+using dkv::TView;
+using dkv::TViewOut;
+
+constexpr int kTargetBlocks = 512;   // prompt-tile workgroups wanted before the sequence loop is split
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+int check_shape(const dualkv_shape* s, bool ctx_call) {
+  if (s == nullptr) return DUALKV_E_INVALID;
+  if (s->ctx_len < 0 || s->n_q_heads <= 0 || s->n_kv_heads <= 0) return DUALKV_E_INVALID;
+  if (s->n_q_heads % s->n_kv_heads != 0) return DUALKV_E_INVALID;
+  if (!ctx_call) {
+    if (s->n_seqs < 1 || s->total_resp < 0 || s->max_resp < 0 || s->max_resp > s->total_resp) return DUALKV_E_INVALID;
+    if (s->total_resp > 0 && s->max_resp == 0) return DUALKV_E_INVALID;
+  }
+  const int d = s->head_dim;
+  if (d != 64 && d != 128 && d != 256 && d != 512) return DUALKV_E_UNSUPPORTED;
+  if (s->window > 0 && d == 512) return DUALKV_E_UNSUPPORTED;
+  return DUALKV_OK;
+}
+
+int check_view(const void* ptr, int64_t ts, int64_t hs, int64_t rows, int d) {
+  if (rows == 0) return DUALKV_OK;
+  if (ptr == nullptr) return DUALKV_E_INVALID;
+  if (reinterpret_cast<uintptr_t>(ptr) % 16 != 0) return DUALKV_E_ALIGN;
+  if (ts % 8 != 0 || hs % 8 != 0) return DUALKV_E_ALIGN;
+  if (ts < d || hs < d) return DUALKV_E_INVALID;
+  return DUALKV_OK;
+}
+int check_in(const dualkv_tin& t, int64_t rows, int d) { return check_view(t.ptr, t.tok_stride, t.head_stride, rows, d); }
+int check_out(const dualkv_tout& t, int64_t rows, int d) { return check_view(t.ptr, t.tok_stride, t.head_stride, rows, d); }
+
+TView view(const dualkv_tin& t) { return TView{static_cast<const dkv::u16*>(t.ptr), t.tok_stride, t.head_stride}; }
+TViewOut view(const dualkv_tout& t) { return TViewOut{static_cast<dkv::u16*>(t.ptr), t.tok_stride, t.head_stride}; }
+
+int check_cu_host(const dualkv_shape* s, const int32_t* cu) {
+  if (cu == nullptr) return DUALKV_OK;
+  if (cu[0] != 0) return DUALKV_E_INVALID;
+  int mx = 0;
+  for (int i = 0; i < s->n_seqs; ++i) {
+    const int r = cu[i + 1] - cu[i];
+    if (r < 0) return DUALKV_E_INVALID;
+    if (r > mx) mx = r;
+  }
+  if (cu[s->n_seqs] != s->total_resp) return DUALKV_E_INVALID;
+  if (mx > s->max_resp) return DUALKV_E_INVALID;
+  return DUALKV_OK;
+}
+
+float resolve_scale(const dualkv_shape* s) {
+  return s->softmax_scale > 0.f ? s->softmax_scale : 1.0f / sqrtf((float)s->head_dim);
+}
+
+// number of parts the sequence loop of a prompt-tile workgroup is cut into
+int ctx_split(const dualkv_shape* s) {
+  if (s->ctx_len == 0) return 1;
+  const int bn = dkv::dkdv_key_tile(s->head_dim);
+  const int64_t blocks = (int64_t)((s->ctx_len + bn - 1) / bn) * s->n_kv_heads;
+  if (blocks >= kTargetBlocks) return 1;
+  int64_t want = (kTargetBlocks + blocks - 1) / blocks;
+  if (want > s->n_seqs) want = s->n_seqs;
+  return (int)(want < 1 ? 1 : want);
+}
+
+struct BwdWorkspace {
+  size_t dvec_off, dvec_bytes, acc_off, acc_bytes, total;
+};
+
+BwdWorkspace bwd_workspace(const dualkv_shape* s, bool ctx_call) {
+  BwdWorkspace w{};
+  const int64_t rows = ctx_call ? s->ctx_len : s->total_resp;
+  w.dvec_off = 0;
+  w.dvec_bytes = align_up((size_t)rows * s->n_q_heads * sizeof(float), 256);
+  w.acc_off = w.dvec_bytes;
+  w.acc_bytes = 0;
+  if (!ctx_call && !(s->flags & DUALKV_FLAG_ACCUM_CTX_F32) && ctx_split(s) > 1)
+    w.acc_bytes = align_up((size_t)s->ctx_len * s->n_kv_heads * s->head_dim * sizeof(float), 256);
+  w.total = w.dvec_bytes + 2 * w.acc_bytes;
+  return w;
+}
+
+int hip_rc(hipError_t e) { return e == hipSuccess ? DUALKV_OK : DUALKV_E_HIP; }
+
+void base_params(AttnParams& p, const dualkv_shape* s) {
+  p = AttnParams{};
+  p.H = s->n_q_heads;
+  p.Hk = s->n_kv_heads;
+  p.G = s->n_q_heads / s->n_kv_heads;
+  p.window = s->window > 0 ? s->window : 0;
+  p.scale = resolve_scale(s);
+  p.scale_log2 = p.scale * dkv::LOG2E;
+  p.n_split = 1;
+}
+
+}  // namespace
+
+extern "C" {
+
+int dualkv_version(void) { return 100; }
+
+const char* dualkv_strerror(int code) {
+  switch (code) {
+    case DUALKV_OK: return "ok";
+    case DUALKV_E_INVALID: return "invalid argument";
+    case DUALKV_E_UNSUPPORTED: return "unsupported head_dim / window combination";
+    case DUALKV_E_WORKSPACE: return "workspace missing or too small";
+    case DUALKV_E_ALIGN: return "pointer not 16-byte aligned or stride not a multiple of 8 elements";
+    case DUALKV_E_HIP: return "HIP runtime error";
+  }
+  return "unknown error";
+}
+
+int dualkv_workspace_bytes(const dualkv_shape* shape, int op, size_t* out_bytes) {
+  if (out_bytes == nullptr) return DUALKV_E_INVALID;
+  const bool ctx_call = (op == DUALKV_OP_CTX_FWD || op == DUALKV_OP_CTX_BWD);
+  if (op < DUALKV_OP_CTX_FWD || op > DUALKV_OP_BWD) return DUALKV_E_INVALID;
+  const int rc = check_shape(shape, ctx_call);
+  if (rc != DUALKV_OK) return rc;
+  if (op == DUALKV_OP_CTX_FWD || op == DUALKV_OP_FWD) {
+    *out_bytes = 0;
+    return DUALKV_OK;
+  }
+  *out_bytes = bwd_workspace(shape, ctx_call).total;
+  return DUALKV_OK;
+}
+
+int dualkv_ctx_fwd(const dualkv_shape* shape, dualkv_tin q_c, dualkv_tin k_c, dualkv_tin v_c, dualkv_tout o_c,
+                   float* lse_c, void* workspace, size_t workspace_bytes, void* stream) {
+  (void)workspace;
+  (void)workspace_bytes;
+  int rc = check_shape(shape, true);
+  if (rc != DUALKV_OK) return rc;
+  const int P = shape->ctx_len, d = shape->head_dim;
+  if (P == 0) return DUALKV_OK;
+  if ((rc = check_in(q_c, P, d)) || (rc = check_in(k_c, P, d)) || (rc = check_in(v_c, P, d)) ||
+      (rc = check_out(o_c, P, d)))
+    return rc;
+  if (lse_c == nullptr) return DUALKV_E_INVALID;
+  AttnParams p;
+  base_params(p, shape);
+  p.q = view(q_c);
+  p.kd = view(k_c);
+  p.vd = view(v_c);
+  p.kc = p.kd;   // unused (ctx_len = 0)
+  p.vc = p.vd;
+  p.out_o = view(o_c);
+  p.lse = lse_c;
+  p.cu = nullptr;
+  p.n_seqs = 1;
+  p.ctx_len = 0;
+  p.total = P;
+  p.max_rows = P;
+  return hip_rc(dkv::launch_fwd(p, d, static_cast<hipStream_t>(stream)));
+}
+
+int dualkv_fwd(const dualkv_shape* shape, dualkv_tin q_d, dualkv_tin k_c, dualkv_tin v_c, dualkv_tin k_d,
+               dualkv_tin v_d, const int32_t* cu_seqlens_dev, const int32_t* cu_seqlens_host, dualkv_tout o_d,
+               float* lse_d, void* workspace, size_t workspace_bytes, void* stream) {
+  (void)workspace;
+  (void)workspace_bytes;
+  int rc = check_shape(shape, false);
+  if (rc != DUALKV_OK) return rc;
+  if ((rc = check_cu_host(shape, cu_seqlens_host))) return rc;
+  const int P = shape->ctx_len, T = shape->total_resp, d = shape->head_dim;
+  if (T == 0) return DUALKV_OK;
+  if (cu_seqlens_dev == nullptr || lse_d == nullptr) return DUALKV_E_INVALID;
+  if ((rc = check_in(q_d, T, d)) || (rc = check_in(k_c, P, d)) || (rc = check_in(v_c, P, d)) ||
+      (rc = check_in(k_d, T, d)) || (rc = check_in(v_d, T, d)) || (rc = check_out(o_d, T, d)))
+    return rc;
+  AttnParams p;
+  base_params(p, shape);
+  p.q = view(q_d);
+  p.kc = view(k_c);
+  p.vc = view(v_c);
+  p.kd = view(k_d);
+  p.vd = view(v_d);
+  p.out_o = view(o_d);
+  p.lse = lse_d;
+  p.cu = cu_seqlens_dev;
+  p.n_seqs = shape->n_seqs;
+  p.ctx_len = P;
+  p.total = T;
+  p.max_rows = shape->max_resp;
+  return hip_rc(dkv::launch_fwd(p, d, static_cast<hipStream_t>(stream)));
+}
+
+int dualkv_ctx_bwd(const dualkv_shape* shape, dualkv_tin do_c, dualkv_tin o_c, const float* lse_c, dualkv_tin q_c,
+                   dualkv_tin k_c, dualkv_tin v_c, dualkv_tout dq_c, dualkv_tout dk_c, dualkv_tout dv_c,
+                   float* dk_c_acc32, float* dv_c_acc32, void* workspace, size_t workspace_bytes, void* stream) {
+  int rc = check_shape(shape, true);
+  if (rc != DUALKV_OK) return rc;
+  const int P = shape->ctx_len, d = shape->head_dim;
+  if (P == 0) return DUALKV_OK;
+  const bool accum = (shape->flags & DUALKV_FLAG_ACCUM_CTX_F32) != 0;
+  if ((rc = check_in(do_c, P, d)) || (rc = check_in(o_c, P, d)) || (rc = check_in(q_c, P, d)) ||
+      (rc = check_in(k_c, P, d)) || (rc = check_in(v_c, P, d)) || (rc = check_out(dq_c, P, d)))
+    return rc;
+  if (lse_c == nullptr) return DUALKV_E_INVALID;
+  if (accum) {
+    if (dk_c_acc32 == nullptr || dv_c_acc32 == nullptr) return DUALKV_E_INVALID;
+    if ((reinterpret_cast<uintptr_t>(dk_c_acc32) | reinterpret_cast<uintptr_t>(dv_c_acc32)) % 16) return DUALKV_E_ALIGN;
+  } else if ((rc = check_out(dk_c, P, d)) || (rc = check_out(dv_c, P, d))) {
+    return rc;
+  }
+  const BwdWorkspace w = bwd_workspace(shape, true);
+  if (workspace == nullptr || workspace_bytes < w.total) return DUALKV_E_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(workspace) % 16) return DUALKV_E_ALIGN;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+
+  AttnParams p;
+  base_params(p, shape);
+  p.q = view(q_c);
+  p.kd = view(k_c);
+  p.vd = view(v_c);
+  p.kc = p.kd;
+  p.vc = p.vd;
+  p.o = view(o_c);
+  p.dout = view(do_c);
+  p.dq = view(dq_c);
+  if (!accum) {
+    p.dkd = view(dk_c);
+    p.dvd = view(dv_c);
+  } else {
+    p.dkd_acc = dk_c_acc32;
+    p.dvd_acc = dv_c_acc32;
+  }
+  p.lse = const_cast<float*>(lse_c);
+  p.dvec = reinterpret_cast<float*>(static_cast<char*>(workspace) + w.dvec_off);
+  p.cu = nullptr;
+  p.n_seqs = 1;
+  p.ctx_len = 0;
+  p.total = P;
+  p.max_rows = P;
+  if ((rc = hip_rc(dkv::launch_dot_do_o(p.dout, p.o, p.dvec, P, p.H, d, st)))) return rc;
+  if ((rc = hip_rc(dkv::launch_dkdv(p, d, st)))) return rc;
+  return hip_rc(dkv::launch_dq(p, d, st));
+}
+
+int dualkv_bwd(const dualkv_shape* shape, dualkv_tin do_d, dualkv_tin o_d, const float* lse_d, dualkv_tin q_d,
+               dualkv_tin k_c, dualkv_tin v_c, dualkv_tin k_d, dualkv_tin v_d, const int32_t* cu_seqlens_dev,
+               const int32_t* cu_seqlens_host, dualkv_tout dq_d, dualkv_tout dk_c, dualkv_tout dv_c, dualkv_tout dk_d,
+               dualkv_tout dv_d, float* dk_c_acc32, float* dv_c_acc32, void* workspace, size_t workspace_bytes,
+               void* stream) {
+  int rc = check_shape(shape, false);
+  if (rc != DUALKV_OK) return rc;
+  if ((rc = check_cu_host(shape, cu_seqlens_host))) return rc;
+  const int P = shape->ctx_len, T = shape->total_resp, d = shape->head_dim;
+  const bool accum = (shape->flags & DUALKV_FLAG_ACCUM_CTX_F32) != 0;
+  if (T > 0) {
+    if (cu_seqlens_dev == nullptr || lse_d == nullptr) return DUALKV_E_INVALID;
+    if ((rc = check_in(do_d, T, d)) || (rc = check_in(o_d, T, d)) || (rc = check_in(q_d, T, d)) ||
+        (rc = check_in(k_d, T, d)) || (rc = check_in(v_d, T, d)) || (rc = check_out(dq_d, T, d)) ||
+        (rc = check_out(dk_d, T, d)) || (rc = check_out(dv_d, T, d)))
+      return rc;
+  }
+  if ((rc = check_in(k_c, P, d)) || (rc = check_in(v_c, P, d))) return rc;
+  if (accum) {
+    if (P > 0 && (dk_c_acc32 == nullptr || dv_c_acc32 == nullptr)) return DUALKV_E_INVALID;
+    if ((reinterpret_cast<uintptr_t>(dk_c_acc32) | reinterpret_cast<uintptr_t>(dv_c_acc32)) % 16) return DUALKV_E_ALIGN;
+  } else if ((rc = check_out(dk_c, P, d)) || (rc = check_out(dv_c, P, d))) {
+    return rc;
+  }
+  const BwdWorkspace w = bwd_workspace(shape, false);
+  if (w.total > 0 && (workspace == nullptr || workspace_bytes < w.total)) return DUALKV_E_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(workspace) % 16) return DUALKV_E_ALIGN;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int64_t n_acc = (int64_t)P * shape->n_kv_heads * d;
+
+  AttnParams p;
+  base_params(p, shape);
+  p.q = view(q_d);
+  p.kc = view(k_c);
+  p.vc = view(v_c);
+  p.kd = view(k_d);
+  p.vd = view(v_d);
+  p.o = view(o_d);
+  p.dout = view(do_d);
+  p.dq = view(dq_d);
+  p.dkd = view(dk_d);
+  p.dvd = view(dv_d);
+  p.lse = const_cast<float*>(lse_d);
+  p.dvec = reinterpret_cast<float*>(static_cast<char*>(workspace) + w.dvec_off);
+  p.cu = cu_seqlens_dev;
+  p.n_seqs = shape->n_seqs;
+  p.ctx_len = P;
+  p.total = T;
+  p.max_rows = shape->max_resp;
+
+  const bool scratch = !accum && w.acc_bytes > 0;
+  if (accum) {
+    p.dkc_acc = dk_c_acc32;
+    p.dvc_acc = dv_c_acc32;
+    p.n_split = ctx_split(shape);
+  } else if (scratch) {
+    p.dkc_acc = reinterpret_cast<float*>(static_cast<char*>(workspace) + w.acc_off);
+    p.dvc_acc = reinterpret_cast<float*>(static_cast<char*>(workspace) + w.acc_off + w.acc_bytes);
+    p.n_split = ctx_split(shape);
+    // zero-initialise the fp32 scratch (Alg. 1, "Require: zero-initialized")
+    if ((rc = hip_rc(dkv::launch_fill_f32(p.dkc_acc, n_acc, 0.f, st)))) return rc;
+    if ((rc = hip_rc(dkv::launch_fill_f32(p.dvc_acc, n_acc, 0.f, st)))) return rc;
+  } else {
+    p.dkc = view(dk_c);
+    p.dvc = view(dv_c);
+  }
+  if (T > 0 && (rc = hip_rc(dkv::launch_dot_do_o(p.dout, p.o, p.dvec, T, p.H, d, st)))) return rc;
+  if ((rc = hip_rc(dkv::launch_dkdv(p, d, st)))) return rc;
+  if (scratch) {
+    // Stage 2 (Alg. 2): cast the accumulated prompt gradients once
+    if ((rc = hip_rc(dkv::launch_convert_ctx(p.dkc_acc, view(dk_c), P, p.Hk, d, 1.0f, st)))) return rc;
+    if ((rc = hip_rc(dkv::launch_convert_ctx(p.dvc_acc, view(dv_c), P, p.Hk, d, 1.0f, st)))) return rc;
+  }
+  if (T > 0) return hip_rc(dkv::launch_dq(p, d, st));
+  return DUALKV_OK;
+}
+
+int dualkv_finalize_ctx_grads(const dualkv_shape* shape, const float* dk_c_acc32, const float* dv_c_acc32,
+                              dualkv_tout dk_c, dualkv_tout dv_c, void* stream) {
+  int rc = check_shape(shape, true);
+  if (rc != DUALKV_OK) return rc;
+  const int P = shape->ctx_len, d = shape->head_dim;
+  if (P == 0) return DUALKV_OK;
+  if (dk_c_acc32 == nullptr || dv_c_acc32 == nullptr) return DUALKV_E_INVALID;
+  if ((reinterpret_cast<uintptr_t>(dk_c_acc32) | reinterpret_cast<uintptr_t>(dv_c_acc32)) % 16) return DUALKV_E_ALIGN;
+  if ((rc = check_out(dk_c, P, d)) || (rc = check_out(dv_c, P, d))) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if ((rc = hip_rc(dkv::launch_convert_ctx(dk_c_acc32, view(dk_c), P, shape->n_kv_heads, d, 1.0f, st)))) return rc;
+  return hip_rc(dkv::launch_convert_ctx(dv_c_acc32, view(dv_c), P, shape->n_kv_heads, d, 1.0f, st));
+}
+
+static int rows_copy_common(bool to_packed, int32_t n_seqs, int32_t ctx_len, int32_t total_resp,
+                            const int32_t* cu, int64_t row_bytes, const void* src, void* dst, int32_t* pos,
+                            void* stream) {
+  if (n_seqs < 1 || ctx_len < 0 || total_resp < 0 || row_bytes <= 0) return DUALKV_E_INVALID;
+  if (row_bytes % 4 != 0) return DUALKV_E_ALIGN;
+  if ((int64_t)ctx_len + total_resp == 0) return DUALKV_OK;
+  if (cu == nullptr || src == nullptr || dst == nullptr) return DUALKV_E_INVALID;
+  if ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) % 4) return DUALKV_E_ALIGN;
+  return hip_rc(dkv::launch_rows_copy(to_packed, n_seqs, ctx_len, total_resp, cu, row_bytes, src, dst, pos,
+                                      static_cast<hipStream_t>(stream)));
+}
+
+int dualkv_repack(int32_t n_seqs, int32_t ctx_len, int32_t total_resp, const int32_t* cu_seqlens_dev,
+                  int64_t row_bytes, const void* standard, void* packed, int32_t* position_ids, void* stream) {
+  return rows_copy_common(true, n_seqs, ctx_len, total_resp, cu_seqlens_dev, row_bytes, standard, packed,
+                          position_ids, stream);
+}
+
+int dualkv_replicate(int32_t n_seqs, int32_t ctx_len, int32_t total_resp, const int32_t* cu_seqlens_dev,
+                     int64_t row_bytes, const void* packed, void* standard, int32_t* position_ids, void* stream) {
+  return rows_copy_common(false, n_seqs, ctx_len, total_resp, cu_seqlens_dev, row_bytes, packed, standard,
+                          position_ids, stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,170 @@
+// Bandwidth-bound helper kernels: D = rowsum(dO * O) (the "dot_do_o" preprocess of Alg. 1), fp32 fill,
+// fp32 -> bf16 cast of the accumulated shared-prompt gradients (Alg. 2) and the layout gathers between
+// the standard packing (Eq. 1) and the single-prompt packing (Eq. 5).
+#include "common.h"
+#include "launch.h"
+
+namespace dkv {
+
+// ---------------------------------------------------------------------------------------------
+// D[h][row] = sum_d dO[row,h,d] * O[row,h,d].  One group of D/8 lanes per (row, head); each lane reads
+// 16 bytes of dO and of O, so a wave reads whole contiguous rows.
+// ---------------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(256) void dot_do_o_kernel(TView dout, TView o, float* __restrict__ dvec, int total,
+                                                       int H) {
+  constexpr int LPR = D / 8;          // lanes per (row, head)
+  constexpr int RPB = 256 / LPR;      // (row, head) pairs per block
+  const int tid = threadIdx.x;
+  const int64_t pair = (int64_t)blockIdx.x * RPB + tid / LPR;
+  const int sub = tid % LPR;
+  float acc = 0.f;
+  const bool ok = pair < (int64_t)total * H;
+  const int64_t row = ok ? pair / H : 0;
+  const int h = ok ? (int)(pair % H) : 0;
+  if (ok) {
+    const u32x4 a = *reinterpret_cast<const u32x4*>(dout.ptr + row * dout.ts + (int64_t)h * dout.hs + sub * 8);
+    const u32x4 b = *reinterpret_cast<const u32x4*>(o.ptr + row * o.ts + (int64_t)h * o.hs + sub * 8);
+    const uint32_t* aw = reinterpret_cast<const uint32_t*>(&a);
+    const uint32_t* bw = reinterpret_cast<const uint32_t*>(&b);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) acc += bf16_lo(aw[i]) * bf16_lo(bw[i]) + bf16_hi(aw[i]) * bf16_hi(bw[i]);
+  }
+#pragma unroll
+  for (int off = LPR / 2; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
+  if (ok && sub == 0) dvec[(int64_t)h * total + row] = acc;
+}
+
+hipError_t launch_dot_do_o(const TView& dout, const TView& o, float* dvec, int total, int H, int head_dim,
+                           hipStream_t st) {
+  const int64_t pairs = (int64_t)total * H;
+  if (pairs == 0) return hipSuccess;
+  const int lpr = head_dim / 8, rpb = 256 / lpr;
+  const unsigned grid = (unsigned)((pairs + rpb - 1) / rpb);
+  switch (head_dim) {
+    case 64:  hipLaunchKernelGGL(dot_do_o_kernel<64>, dim3(grid), dim3(256), 0, st, dout, o, dvec, total, H); break;
+    case 128: hipLaunchKernelGGL(dot_do_o_kernel<128>, dim3(grid), dim3(256), 0, st, dout, o, dvec, total, H); break;
+    case 256: hipLaunchKernelGGL(dot_do_o_kernel<256>, dim3(grid), dim3(256), 0, st, dout, o, dvec, total, H); break;
+    case 512: hipLaunchKernelGGL(dot_do_o_kernel<512>, dim3(grid), dim3(256), 0, st, dout, o, dvec, total, H); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void fill_f32_kernel(float* __restrict__ ptr, int64_t n, float value) {
+  const int64_t stride = (int64_t)gridDim.x * 256 * 4;
+  for (int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4; i < n; i += stride) {
+    if (i + 4 <= n) {
+      f32x4 v = {value, value, value, value};
+      *reinterpret_cast<f32x4*>(ptr + i) = v;
+    } else {
+      for (int64_t j = i; j < n; ++j) ptr[j] = value;
+    }
+  }
+}
+
+hipError_t launch_fill_f32(float* ptr, int64_t n, float value, hipStream_t st) {
+  if (n <= 0) return hipSuccess;
+  int64_t blocks = (n + 1023) / 1024;
+  if (blocks > 8192) blocks = 8192;
+  hipLaunchKernelGGL(fill_f32_kernel, dim3((unsigned)blocks), dim3(256), 0, st, ptr, n, value);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// acc (P, Hk, D) fp32 contiguous -> out (P, Hk, D) bf16 strided, multiplied by `mul`
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void convert_ctx_kernel(const float* __restrict__ acc, TViewOut out, int64_t n8,
+                                                          int Hk, int D, float mul) {
+  const int64_t stride = (int64_t)gridDim.x * 256;
+  const int cpr = D / 8;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n8; i += stride) {
+    const int ch = (int)(i % cpr);
+    const int64_t rh = i / cpr;
+    const int h = (int)(rh % Hk);
+    const int64_t row = rh / Hk;
+    const f32x4 a = *reinterpret_cast<const f32x4*>(acc + i * 8);
+    const f32x4 b = *reinterpret_cast<const f32x4*>(acc + i * 8 + 4);
+    u32x4 w;
+    w.x = pack2_bf16(a[0] * mul, a[1] * mul);
+    w.y = pack2_bf16(a[2] * mul, a[3] * mul);
+    w.z = pack2_bf16(b[0] * mul, b[1] * mul);
+    w.w = pack2_bf16(b[2] * mul, b[3] * mul);
+    *reinterpret_cast<u32x4*>(out.ptr + row * out.ts + (int64_t)h * out.hs + ch * 8) = w;
+  }
+}
+
+hipError_t launch_convert_ctx(const float* acc, const TViewOut& out, int P, int Hk, int head_dim, float mul,
+                              hipStream_t st) {
+  const int64_t n8 = (int64_t)P * Hk * head_dim / 8;
+  if (n8 == 0) return hipSuccess;
+  int64_t blocks = (n8 + 255) / 256;
+  if (blocks > 16384) blocks = 16384;
+  hipLaunchKernelGGL(convert_ctx_kernel, dim3((unsigned)blocks), dim3(256), 0, st, acc, out, n8, Hk, head_dim, mul);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// Layout gathers.  Destination-row driven: one workgroup per destination row finds its source row
+// (binary search in cu_seqlens) and copies row_bytes.
+//   to_packed : dst = single-prompt packing, src = standard packing
+//   !to_packed: dst = standard packing,      src = single-prompt packing
+// ---------------------------------------------------------------------------------------------
+template <typename VEC>
+__global__ __launch_bounds__(256) void rows_copy_kernel(bool to_packed, int n_seqs, int P, int total_resp,
+                                                        const int32_t* __restrict__ cu, int64_t row_vecs,
+                                                        const VEC* __restrict__ src, VEC* __restrict__ dst,
+                                                        int32_t* __restrict__ pos_ids) {
+  const int64_t drow = blockIdx.x;
+  int64_t srow;
+  int pos;
+  if (to_packed) {
+    if (drow < P) {
+      srow = drow;   // prompt copy of sequence 0 (cu[0] == 0)
+      pos = (int)drow;
+    } else {
+      const int x = (int)(drow - P);   // packed response row
+      int lo = 0, hi = n_seqs;         // find i with cu[i] <= x < cu[i+1]
+      while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (cu[mid] <= x) lo = mid; else hi = mid;
+      }
+      srow = (int64_t)(lo + 1) * P + x;
+      pos = P + (x - cu[lo]);
+    }
+  } else {
+    // standard row: sequence i starts at i*P + cu[i]
+    int lo = 0, hi = n_seqs;
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if ((int64_t)mid * P + cu[mid] <= drow) lo = mid; else hi = mid;
+    }
+    const int64_t off = drow - ((int64_t)lo * P + cu[lo]);
+    pos = (int)off;
+    srow = off < P ? off : (int64_t)P + cu[lo] + (off - P);
+  }
+  const VEC* s = src + srow * row_vecs;
+  VEC* d = dst + drow * row_vecs;
+  for (int64_t i = threadIdx.x; i < row_vecs; i += 256) d[i] = s[i];
+  if (pos_ids != nullptr && threadIdx.x == 0) pos_ids[drow] = pos;
+}
+
+hipError_t launch_rows_copy(bool to_packed, int n_seqs, int ctx_len, int total_resp, const int32_t* cu,
+                            int64_t row_bytes, const void* src, void* dst, int32_t* pos_ids, hipStream_t st) {
+  const int64_t drows = to_packed ? (int64_t)ctx_len + total_resp : (int64_t)n_seqs * ctx_len + total_resp;
+  if (drows == 0) return hipSuccess;
+  const bool v16 = (row_bytes % 16 == 0) && (((uintptr_t)src | (uintptr_t)dst) % 16 == 0);
+  if (v16) {
+    hipLaunchKernelGGL(rows_copy_kernel<u32x4>, dim3((unsigned)drows), dim3(256), 0, st, to_packed, n_seqs, ctx_len,
+                       total_resp, cu, row_bytes / 16, static_cast<const u32x4*>(src), static_cast<u32x4*>(dst),
+                       pos_ids);
+  } else {
+    hipLaunchKernelGGL(rows_copy_kernel<uint32_t>, dim3((unsigned)drows), dim3(256), 0, st, to_packed, n_seqs, ctx_len,
+                       total_resp, cu, row_bytes / 4, static_cast<const uint32_t*>(src), static_cast<uint32_t*>(dst),
+                       pos_ids);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace dkv

@@ -1,0 +1,22 @@
+// Host-side launch entry points of the kernel translation units.
+#pragma once
+#include <hip/hip_runtime.h>
+#include "common.h"
+
+namespace dkv {
+
+hipError_t launch_fwd(const AttnParams& p, int head_dim, hipStream_t st);
+hipError_t launch_dq(const AttnParams& p, int head_dim, hipStream_t st);
+hipError_t launch_dkdv(const AttnParams& p, int head_dim, hipStream_t st);
+// key tile (rows of K/V owned by one workgroup) of the dK/dV kernel for a head dim
+int dkdv_key_tile(int head_dim);
+
+hipError_t launch_dot_do_o(const TView& dout, const TView& o, float* dvec, int total, int H, int head_dim,
+                           hipStream_t st);
+hipError_t launch_fill_f32(float* ptr, int64_t n, float value, hipStream_t st);
+hipError_t launch_convert_ctx(const float* acc, const TViewOut& out, int P, int Hk, int head_dim, float mul,
+                              hipStream_t st);
+hipError_t launch_rows_copy(bool to_packed, int n_seqs, int ctx_len, int total_resp, const int32_t* cu,
+                            int64_t row_bytes, const void* src, void* dst, int32_t* pos_ids, hipStream_t st);
+
+}  // namespace dkv

@@ -1,0 +1,115 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 oracle, element by element, at sizes the
+oracle finishes in seconds: config 1, shrunk replicas of configs 2-5 (odd P and R -> both partial tiles),
+and edge cases (P = 0, empty responses, N = 1, G in {1, 8}, windows across the prompt/response seam)."""
+import numpy as np
+import pytest
+
+from paper_2605_15422_amd import workloads as W
+
+import parity_util as PU
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("name", ["cfg1_tiny", "cfg2_small", "cfg3_small", "cfg4_small", "cfg5a_small",
+                                  "cfg5b_small"])
+def test_config_parity(name):
+    print("case", name, flush=True)
+    PU.full_parity(W.make_workload(W.CONFIGS[name]))
+
+
+@pytest.mark.parametrize("name", ["cfg1_tiny", "cfg3_small", "cfg5b_small"])
+def test_fp32_joint_accumulation(name):
+    from paper_2605_15422_amd import binding as B
+    print("case accum", name, flush=True)
+    PU.full_parity(W.make_workload(W.CONFIGS[name]), flags=B.FLAG_ACCUM_CTX_F32)
+
+
+EDGE = [
+    # name, N, P, lens, H, Hk, d, window
+    ("p0_varlen", 3, 0, [70, 1, 130], 4, 2, 64, 0),
+    ("empty_resp", 4, 100, [0, 33, 0, 65], 4, 4, 64, 0),
+    ("n1_r1", 1, 77, [1], 2, 1, 128, 0),
+    ("g8", 2, 200, [40, 90], 8, 1, 128, 0),
+    ("g1_d256", 2, 130, [64, 31], 2, 2, 256, 0),
+    ("g3", 2, 96, [50, 20], 6, 2, 64, 0),
+    ("win_small", 2, 150, [120, 200], 4, 2, 64, 37),
+    ("win_seam", 2, 300, [90, 260], 4, 2, 128, 128),
+    ("win_huge", 2, 100, [60, 70], 4, 2, 256, 4096),
+    ("d512_tail", 2, 65, [33, 70], 2, 1, 512, 0),
+    ("exact_tiles", 2, 256, [128, 64], 4, 2, 128, 0),
+]
+
+
+@pytest.mark.parametrize("case", EDGE, ids=[c[0] for c in EDGE])
+def test_edge_cases(case):
+    name, N, P, lens, H, Hk, d, win = case
+    print("case", name, flush=True)
+    shape = W.Shape(name, N, P, 0, 0, H, Hk, d, win, seed=4242 + len(name))
+    wl = W.make_workload(shape, resp_lens=np.asarray(lens))
+    PU.full_parity(wl)
+
+
+def test_strided_views_of_one_packed_qkv_buffer():
+    """Zero-copy prompt/response views of one packed (T, H+2Hk, d) buffer (App. A.3 "QKV split")."""
+    import torch
+    from paper_2605_15422_amd import binding as B, runner
+    print("case packed_qkv", flush=True)
+    shape = W.Shape("packed_qkv", 3, 90, 0, 0, 4, 2, 128, 0, seed=77)
+    wl = W.make_workload(shape, resp_lens=np.asarray([40, 70, 9]))
+    dg = B.upload(wl)
+    P, T, H, Hk, d = 90, wl.total_resp, 4, 2, 128
+    packed = torch.empty((P + T, H + 2 * Hk, d), dtype=torch.bfloat16, device="cuda")
+    packed[:P, :H] = dg.q_c
+    packed[:P, H:H + Hk] = dg.k_c
+    packed[:P, H + Hk:] = dg.v_c
+    packed[P:, :H] = dg.q_d
+    packed[P:, H:H + Hk] = dg.k_d
+    packed[P:, H + Hk:] = dg.v_d
+    dg2 = B.DeviceGroup(dg.shape_c, packed[:P, :H], packed[:P, H:H + Hk], packed[:P, H + Hk:],
+                        packed[P:, :H], packed[P:, H:H + Hk], packed[P:, H + Hk:], dg.do_c, dg.do_d,
+                        dg.cu_dev, dg.cu_host)
+    b1 = runner.alloc(dg)
+    runner.layer_step(dg, b1)
+    # outputs as views of one packed gradient buffer as well
+    gbuf = torch.full((P + T, H + 2 * Hk, d), float("nan"), dtype=torch.bfloat16, device="cuda")
+    b2 = runner.alloc(dg2)
+    b2.dq_c, b2.dk_c1, b2.dv_c1 = gbuf[:P, :H], gbuf[:P, H:H + Hk], gbuf[:P, H + Hk:]
+    b2.dq_d, b2.dk_d, b2.dv_d = gbuf[P:, :H], gbuf[P:, H:H + Hk], gbuf[P:, H + Hk:]
+    runner.layer_step(dg2, b2)
+    torch.cuda.synchronize()
+    for n in ("o_c", "o_d", "lse_c", "lse_d", "dq_c", "dq_d", "dk_c1", "dv_c1", "dk_c2", "dv_c2", "dk_d", "dv_d"):
+        a, c = getattr(b1, n), getattr(b2, n)
+        assert torch.equal(a.view(torch.int16) if a.dtype == torch.bfloat16 else a,
+                           c.contiguous().view(torch.int16) if c.dtype == torch.bfloat16 else c), n
+
+
+def test_layout_kernels():
+    import torch
+    from paper_2605_15422_amd import binding as B
+    print("case layout", flush=True)
+    rng = np.random.default_rng(5)
+    N, P = 4, 37
+    lens = np.array([5, 0, 19, 8])
+    cu = np.zeros(N + 1, dtype=np.int32)
+    cu[1:] = np.cumsum(lens)
+    T = int(cu[-1])
+    for row_bytes in (24, 4096):
+        n16 = row_bytes // 2
+        x_c = rng.integers(0, 65535, size=(P, n16)).astype(np.uint16)
+        x_d = rng.integers(0, 65535, size=(T, n16)).astype(np.uint16)
+        std, cu_rep = W.replicated_layout(P, cu, x_c, x_d)
+        cu_dev = torch.from_numpy(cu).cuda()
+        packed = torch.from_numpy(np.concatenate([x_c, x_d]).view(np.int16)).cuda()
+        out = torch.zeros((N * P + T, n16), dtype=torch.int16, device="cuda")
+        pos = torch.full((N * P + T,), -1, dtype=torch.int32, device="cuda")
+        B.dualkv_replicate(N, P, T, cu_dev, row_bytes, packed, out, pos)
+        assert np.array_equal(out.cpu().numpy().view(np.uint16), std)
+        want_pos = np.concatenate([np.arange(P + l) for l in lens])
+        assert np.array_equal(pos.cpu().numpy(), want_pos)
+        back = torch.zeros((P + T, n16), dtype=torch.int16, device="cuda")
+        pos2 = torch.full((P + T,), -1, dtype=torch.int32, device="cuda")
+        B.dualkv_repack(N, P, T, cu_dev, row_bytes, out, back, pos2)
+        assert torch.equal(back, packed)
+        want2 = np.concatenate([np.arange(P)] + [P + np.arange(l) for l in lens])
+        assert np.array_equal(pos2.cpu().numpy(), want2)
