@@ -90,14 +90,20 @@ def _tin(t) -> TIn:
     """(rows, heads, d) bf16 tensor view -> pointer + element strides (None -> NULL)."""
     if t is None:
         return TIn(None, 0, 0)
-    assert t.dtype == torch.bfloat16 and t.dim() == 3 and (t.shape[2] == 1 or t.stride(2) == 1)
+    assert t.dtype == torch.bfloat16 and t.dim() == 3
+    if t.numel() == 0:   # empty region (e.g. P = 0): NULL with the strides of a contiguous tensor
+        return TIn(None, t.shape[1] * t.shape[2], t.shape[2])
+    assert t.stride(2) == 1
     return TIn(t.data_ptr(), t.stride(0), t.stride(1))
 
 
 def _tout(t) -> TOut:
     if t is None:
         return TOut(None, 0, 0)
-    assert t.dtype == torch.bfloat16 and t.dim() == 3 and (t.shape[2] == 1 or t.stride(2) == 1)
+    assert t.dtype == torch.bfloat16 and t.dim() == 3
+    if t.numel() == 0:
+        return TOut(None, t.shape[1] * t.shape[2], t.shape[2])
+    assert t.stride(2) == 1
     return TOut(t.data_ptr(), t.stride(0), t.stride(1))
 
 
