@@ -1,0 +1,254 @@
+#!/usr/bin/env python3
+"""Benchmark of the shared-prompt attention hot path on one MI355X.
+
+A step = one pass of the whole path over one synthetic group: Call 1 forward, Call 2 forward, Call 2
+backward (D preprocess, dK/dV, dQ), Call 1 backward.  Inputs are resident in HBM before timing starts.
+Prints ONE JSON line (metric, value = algorithmic TFLOP/s of the whole layer, ms_per_step = ms/layer, the
+roofline of the dominant kernel, the N-copy reference point and the CPU-oracle baseline).
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config cfg2_qwen8b] [--no-ncopy] [--no-cpu]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16
+HBM_PEAK_GBS = 8000.0
+
+
+def _events(n):
+    import torch
+    return [torch.cuda.Event(enable_timing=True) for _ in range(n)]
+
+
+def time_layer(dg, bufs, steps, warmup):
+    """Times `steps` layer passes; returns (ms_per_step, per-stage average ms).
+
+    The Call-2 / Call-1 backward is issued stage by stage (same kernels, same order as the plain call) so
+    that HIP events on the launch stream bracket every kernel of the path.
+    """
+    import torch
+    from paper_2605_15422_amd import binding as B
+
+    s = dg.shape_c
+    base = s.flags
+
+    def shape_with(flags):
+        c = type(s).from_buffer_copy(bytes(s))
+        c.flags = base | flags
+        return c
+
+    s_pre = shape_with(B.FLAG_SKIP_DQ | B.FLAG_SKIP_DKDV)
+    s_dkdv = shape_with(B.FLAG_SKIP_PRE | B.FLAG_SKIP_DQ)
+    s_dq = shape_with(B.FLAG_SKIP_PRE | B.FLAG_SKIP_DKDV)
+    names = ["ctx_fwd", "fwd", "bwd_pre", "bwd_dkdv", "bwd_dq", "ctx_bwd_pre", "ctx_bwd_dkdv", "ctx_bwd_dq"]
+
+    def bwd2(sh):
+        B.dualkv_bwd(sh, dg.do_d, bufs.o_d, bufs.lse_d, dg.q_d, dg.k_c, dg.v_c, dg.k_d, dg.v_d, dg.cu_dev, None,
+                     bufs.dq_d, bufs.dk_c2, bufs.dv_c2, bufs.dk_d, bufs.dv_d, None, None, bufs.ws_bwd)
+
+    def bwd1(sh):
+        B.dualkv_ctx_bwd(sh, dg.do_c, bufs.o_c, bufs.lse_c, dg.q_c, dg.k_c, dg.v_c, bufs.dq_c, bufs.dk_c1,
+                         bufs.dv_c1, None, None, bufs.ws_ctx_bwd)
+
+    def one_step(ev):
+        k = 0
+        ev[k].record(); k += 1
+        if s.ctx_len > 0:
+            B.dualkv_ctx_fwd(s, dg.q_c, dg.k_c, dg.v_c, bufs.o_c, bufs.lse_c)
+        ev[k].record(); k += 1
+        B.dualkv_fwd(s, dg.q_d, dg.k_c, dg.v_c, dg.k_d, dg.v_d, dg.cu_dev, None, bufs.o_d, bufs.lse_d)
+        ev[k].record(); k += 1
+        for sh in (s_pre, s_dkdv, s_dq):
+            bwd2(sh)
+            ev[k].record(); k += 1
+        for sh in (s_pre, s_dkdv, s_dq):
+            if s.ctx_len > 0:
+                bwd1(sh)
+            ev[k].record(); k += 1
+
+    dummy = _events(9)
+    for _ in range(warmup):
+        one_step(dummy)
+    torch.cuda.synchronize()
+    evs = [_events(9) for _ in range(steps)]
+    t0 = time.perf_counter()
+    for i in range(steps):
+        one_step(evs[i])
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    gpu_ms = evs[0][0].elapsed_time(evs[-1][-1])
+    stage = {n: 0.0 for n in names}
+    for ev in evs:
+        for j, n in enumerate(names):
+            stage[n] += ev[j].elapsed_time(ev[j + 1]) / steps
+    return max(gpu_ms, 0.0) / steps, wall_ms / steps, stage
+
+
+def time_ncopy(wl, steps, warmup):
+    """The same kernels on the explicitly replicated N x (P + R_i) layout (ctx_len = 0)."""
+    import numpy as np
+    import torch
+    from paper_2605_15422_amd import binding as B, runner
+
+    s = wl.shape
+    N, P, T = s.n_seqs, s.ctx_len, wl.total_resp
+    cu_dev = torch.from_numpy(wl.cu_seqlens.copy()).cuda()
+    cu_rep = np.zeros(N + 1, dtype=np.int32)
+    cu_rep[1:] = np.cumsum(P + wl.resp_lens)
+    rows = int(cu_rep[-1])
+
+    def rep(x_c, x_d):
+        packed = torch.cat([B.bf16_from_bits(x_c), B.bf16_from_bits(x_d)], dim=0)
+        out = torch.empty((rows,) + tuple(packed.shape[1:]), dtype=torch.bfloat16, device="cuda")
+        B.dualkv_replicate(N, P, T, cu_dev, packed.shape[1] * packed.shape[2] * 2, packed, out)
+        return out
+
+    q, k, v, do = rep(wl.q_c, wl.q_d), rep(wl.k_c, wl.k_d), rep(wl.v_c, wl.v_d), rep(wl.do_c, wl.do_d)
+    H, Hk, d = s.n_q_heads, s.n_kv_heads, s.head_dim
+    shp = B.make_shape(N, 0, rows, int((P + wl.resp_lens).max()), H, Hk, d, s.window, wl.scale, 0)
+    empty_q = torch.empty((0, H, d), dtype=torch.bfloat16, device="cuda")
+    empty_k = torch.empty((0, Hk, d), dtype=torch.bfloat16, device="cuda")
+    dg = B.DeviceGroup(shp, empty_q, empty_k, empty_k, q, k, v, empty_q, do, torch.from_numpy(cu_rep).cuda(), cu_rep)
+    bufs = runner.alloc(dg, poison=False)
+
+    def step():
+        runner.forward(dg, bufs, call1=False)
+        runner.backward(dg, bufs, call1=False)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = _events(2)
+    e0.record()
+    for _ in range(steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / steps
+
+
+def cpu_baseline(wl, max_tokens=9216):
+    """The fp64 oracle timed on this host: replica 0, KV head 0 with its query heads, fwd + bwd."""
+    import numpy as np
+    from oracle import attention_oracle as orc
+    from paper_2605_15422_amd import workloads as W
+
+    s = wl.shape
+    P, G = s.ctx_len, s.group
+    R0 = int(wl.resp_lens[0])
+    f = W.bf16_bits_to_f64
+    q = np.concatenate([f(wl.q_c[:, :G]), f(wl.q_d[:R0, :G])])[:max_tokens]
+    k = np.concatenate([f(wl.k_c[:, :1]), f(wl.k_d[:R0, :1])])[:max_tokens]
+    v = np.concatenate([f(wl.v_c[:, :1]), f(wl.v_d[:R0, :1])])[:max_tokens]
+    do = np.concatenate([f(wl.do_c[:, :G]), f(wl.do_d[:R0, :G])])[:max_tokens]
+    S = q.shape[0]
+    t0 = time.perf_counter()
+    orc.attn_fwd_seq(q, k, v, wl.scale, s.window)
+    orc.attn_bwd_seq(q, k, v, do, wl.scale, s.window)
+    dt = time.perf_counter() - t0
+    pairs = orc.visible_pairs_call1(S, s.window)
+    flops = 14 * s.head_dim * pairs * G
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+            "seconds": round(dt, 2),
+            "sample": "numpy fp64 dense fwd+bwd of the first %d tokens of replica 0 (prompt + response 0), "
+                      "KV head 0 with its %d query heads; algorithmic flops = 14*d*visible pairs" % (S, G)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="cfg2_qwen8b")
+    ap.add_argument("--no-ncopy", action="store_true")
+    ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--ncopy-steps", type=int, default=2)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (one GPU per box; no collectives are built); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2605_15422_amd import accounting as acc
+    from paper_2605_15422_amd import binding as B, runner
+    from paper_2605_15422_amd import workloads as W
+
+    torch.cuda.set_device(0)
+    shape = W.CONFIGS[args.config]
+    wl = W.make_workload(shape)
+    fl = acc.layer_flops(shape, wl.resp_lens)
+    dg = B.upload(wl)
+    bufs = runner.alloc(dg, poison=False)
+    torch.cuda.synchronize()
+
+    ms, wall_ms, stage = time_layer(dg, bufs, args.steps, args.warmup)
+
+    # dominant kernel and its roofline (MFMA bound: algorithmic flops of that kernel / its duration)
+    d, H = shape.head_dim, shape.n_q_heads
+    kern_flops = {
+        "ctx_fwd": 4 * d * H * fl["pairs_call1"], "fwd": 4 * d * H * fl["pairs_call2"],
+        "bwd_dkdv": 8 * d * H * fl["pairs_call2"], "bwd_dq": 2 * d * H * fl["pairs_call2"],
+        "ctx_bwd_dkdv": 8 * d * H * fl["pairs_call1"], "ctx_bwd_dq": 2 * d * H * fl["pairs_call1"],
+    }
+    dom = max(kern_flops, key=lambda n: stage[n])
+    achieved = kern_flops[dom] / (stage[dom] * 1e-3) / 1e12 if stage[dom] > 0 else 0.0
+    kernel_names = {"ctx_fwd": "fwd_kernel (Call 1)", "fwd": "fwd_kernel (Call 2)",
+                    "bwd_dkdv": "dkdv_kernel (Call 2)", "bwd_dq": "dq_kernel (Call 2)",
+                    "ctx_bwd_dkdv": "dkdv_kernel (Call 1)", "ctx_bwd_dq": "dq_kernel (Call 1)"}
+    roofline = {"bound": "mfma", "kernel": kernel_names[dom], "achieved": round(achieved, 2),
+                "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
+                "traffic": None, "kernel_ms": round(stage[dom], 4),
+                "algorithmic_flops_per_launch": kern_flops[dom]}
+
+    tflops = fl["layer"] / (ms * 1e-3) / 1e12
+    out = {
+        "metric": "DualKV attn fwd+bwd ms/layer & TFLOP/s (MFMA util) vs N-copy attention",
+        "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "%s: N=%d P=%d R=[%d,%d] (sum %d) H=%d Hk=%d d=%d window=%d, Q/K/V/dO ~ N(0,1) seed %d" % (
+            shape.name, shape.n_seqs, shape.ctx_len, int(wl.resp_lens.min()), int(wl.resp_lens.max()),
+            wl.total_resp, shape.n_q_heads, shape.n_kv_heads, d, shape.window, shape.seed),
+            "packed_tokens": shape.ctx_len + wl.total_resp},
+        "frac_mfma_peak": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4),
+        "layer_tflop": round(fl["layer"] / 1e12, 3),
+        "wall_ms_per_step": round(wall_ms, 4),
+        "stage_ms": {k: round(v, 4) for k, v in stage.items()},
+        "stage_tflops": {k: round(kern_flops[k] / (stage[k] * 1e-3) / 1e12, 1) for k in kern_flops if stage[k] > 0},
+        "fwd_ms": round(stage["ctx_fwd"] + stage["fwd"], 4),
+        "bwd_ms": round(sum(stage[k] for k in stage if "bwd" in k), 4),
+        "roofline": roofline,
+    }
+    pre_bytes = 2 * wl.total_resp * H * d * 2 + wl.total_resp * H * 4
+    if stage["bwd_pre"] > 0:
+        out["preprocess_gbs"] = round(pre_bytes / (stage["bwd_pre"] * 1e-3) / 1e9, 1)
+
+    if not args.no_ncopy:
+        del bufs
+        torch.cuda.empty_cache()
+        nms = time_ncopy(wl, args.ncopy_steps, 1)
+        out["ncopy"] = {"ms_per_step": round(nms, 3), "tflop": round(fl["ncopy"] / 1e12, 3),
+                        "tflops": round(fl["ncopy"] / (nms * 1e-3) / 1e12, 2), "speedup_dualkv": round(nms / ms, 3),
+                        "flop_ratio": round(fl["ncopy"] / fl["layer"], 3),
+                        "what": "same kernels on the replicated N x (P+R_i) layout (ctx_len=0), fwd+bwd"}
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(wl)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

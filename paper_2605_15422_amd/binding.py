@@ -26,6 +26,9 @@ lib = C.CDLL(LIB_PATH)
 OK, E_INVALID, E_UNSUPPORTED, E_WORKSPACE, E_ALIGN, E_HIP = 0, -1, -2, -3, -4, -5
 OP_CTX_FWD, OP_CTX_BWD, OP_FWD, OP_BWD = 0, 1, 2, 3
 FLAG_ACCUM_CTX_F32 = 1
+FLAG_SKIP_DQ = 2
+FLAG_SKIP_DKDV = 4
+FLAG_SKIP_PRE = 8
 
 EXPORTS = ["dualkv_workspace_bytes", "dualkv_ctx_fwd", "dualkv_ctx_bwd", "dualkv_fwd", "dualkv_bwd",
            "dualkv_finalize_ctx_grads", "dualkv_repack", "dualkv_replicate", "dualkv_strerror",

@@ -241,9 +241,12 @@ int dualkv_ctx_bwd(const dualkv_shape* shape, dualkv_tin do_c, dualkv_tin o_c, c
   p.ctx_len = 0;
   p.total = P;
   p.max_rows = P;
-  if ((rc = hip_rc(dkv::launch_dot_do_o(p.dout, p.o, p.dvec, P, p.H, d, st)))) return rc;
-  if ((rc = hip_rc(dkv::launch_dkdv(p, d, st)))) return rc;
-  return hip_rc(dkv::launch_dq(p, d, st));
+  const bool do_dq = !(shape->flags & DUALKV_FLAG_SKIP_DQ), do_dkdv = !(shape->flags & DUALKV_FLAG_SKIP_DKDV);
+  if (!(shape->flags & DUALKV_FLAG_SKIP_PRE) && (rc = hip_rc(dkv::launch_dot_do_o(p.dout, p.o, p.dvec, P, p.H, d, st))))
+    return rc;
+  if (do_dkdv && (rc = hip_rc(dkv::launch_dkdv(p, d, st)))) return rc;
+  if (do_dq) return hip_rc(dkv::launch_dq(p, d, st));
+  return DUALKV_OK;
 }
 
 int dualkv_bwd(const dualkv_shape* shape, dualkv_tin do_d, dualkv_tin o_d, const float* lse_d, dualkv_tin q_d,
@@ -306,20 +309,25 @@ int dualkv_bwd(const dualkv_shape* shape, dualkv_tin do_d, dualkv_tin o_d, const
     p.dvc_acc = reinterpret_cast<float*>(static_cast<char*>(workspace) + w.acc_off + w.acc_bytes);
     p.n_split = ctx_split(shape);
     // zero-initialise the fp32 scratch (Alg. 1, "Require: zero-initialized")
-    if ((rc = hip_rc(dkv::launch_fill_f32(p.dkc_acc, n_acc, 0.f, st)))) return rc;
-    if ((rc = hip_rc(dkv::launch_fill_f32(p.dvc_acc, n_acc, 0.f, st)))) return rc;
+    if (!(shape->flags & DUALKV_FLAG_SKIP_DKDV)) {
+      if ((rc = hip_rc(dkv::launch_fill_f32(p.dkc_acc, n_acc, 0.f, st)))) return rc;
+      if ((rc = hip_rc(dkv::launch_fill_f32(p.dvc_acc, n_acc, 0.f, st)))) return rc;
+    }
   } else {
     p.dkc = view(dk_c);
     p.dvc = view(dv_c);
   }
-  if (T > 0 && (rc = hip_rc(dkv::launch_dot_do_o(p.dout, p.o, p.dvec, T, p.H, d, st)))) return rc;
-  if ((rc = hip_rc(dkv::launch_dkdv(p, d, st)))) return rc;
-  if (scratch) {
+  const bool do_dq = !(shape->flags & DUALKV_FLAG_SKIP_DQ), do_dkdv = !(shape->flags & DUALKV_FLAG_SKIP_DKDV);
+  if (T > 0 && !(shape->flags & DUALKV_FLAG_SKIP_PRE) &&
+      (rc = hip_rc(dkv::launch_dot_do_o(p.dout, p.o, p.dvec, T, p.H, d, st))))
+    return rc;
+  if (do_dkdv && (rc = hip_rc(dkv::launch_dkdv(p, d, st)))) return rc;
+  if (scratch && do_dkdv) {
     // Stage 2 (Alg. 2): cast the accumulated prompt gradients once
     if ((rc = hip_rc(dkv::launch_convert_ctx(p.dkc_acc, view(dk_c), P, p.Hk, d, 1.0f, st)))) return rc;
     if ((rc = hip_rc(dkv::launch_convert_ctx(p.dvc_acc, view(dv_c), P, p.Hk, d, 1.0f, st)))) return rc;
   }
-  if (T > 0) return hip_rc(dkv::launch_dq(p, d, st));
+  if (T > 0 && do_dq) return hip_rc(dkv::launch_dq(p, d, st));
   return DUALKV_OK;
 }
 
