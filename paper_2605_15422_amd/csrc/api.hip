@@ -91,6 +91,11 @@ BwdWorkspace bwd_workspace(const dualkv_shape* s, bool ctx_call) {
 
 int hip_rc(hipError_t e) { return e == hipSuccess ? DUALKV_OK : DUALKV_E_HIP; }
 
+hipError_t run_fwd(const AttnParams& p, int d, hipStream_t st) {
+  if (d <= 128) return dkv::launch_fwd2(p, d, st);
+  return dkv::launch_fwd(p, d, st);
+}
+
 void base_params(AttnParams& p, const dualkv_shape* s) {
   p = AttnParams{};
   p.H = s->n_q_heads;
@@ -160,7 +165,7 @@ int dualkv_ctx_fwd(const dualkv_shape* shape, dualkv_tin q_c, dualkv_tin k_c, du
   p.ctx_len = 0;
   p.total = P;
   p.max_rows = P;
-  return hip_rc(dkv::launch_fwd(p, d, static_cast<hipStream_t>(stream)));
+  return hip_rc(run_fwd(p, d, static_cast<hipStream_t>(stream)));
 }
 
 int dualkv_fwd(const dualkv_shape* shape, dualkv_tin q_d, dualkv_tin k_c, dualkv_tin v_c, dualkv_tin k_d,
@@ -191,7 +196,7 @@ int dualkv_fwd(const dualkv_shape* shape, dualkv_tin q_d, dualkv_tin k_c, dualkv
   p.ctx_len = P;
   p.total = T;
   p.max_rows = shape->max_resp;
-  return hip_rc(dkv::launch_fwd(p, d, static_cast<hipStream_t>(stream)));
+  return hip_rc(run_fwd(p, d, static_cast<hipStream_t>(stream)));
 }
 
 int dualkv_ctx_bwd(const dualkv_shape* shape, dualkv_tin do_c, dualkv_tin o_c, const float* lse_c, dualkv_tin q_c,

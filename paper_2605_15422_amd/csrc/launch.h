@@ -6,6 +6,8 @@
 namespace dkv {
 
 hipError_t launch_fwd(const AttnParams& p, int head_dim, hipStream_t st);
+// tuned forward for head dims 64 / 128
+hipError_t launch_fwd2(const AttnParams& p, int head_dim, hipStream_t st);
 hipError_t launch_dq(const AttnParams& p, int head_dim, hipStream_t st);
 hipError_t launch_dkdv(const AttnParams& p, int head_dim, hipStream_t st);
 // key tile (rows of K/V owned by one workgroup) of the dK/dV kernel for a head dim

@@ -14,6 +14,7 @@
 // the B operand of O^T += V^T P^T.
 #include "common.h"
 #include "launch.h"
+#include "qsched.h"
 
 namespace dkv {
 
@@ -31,83 +32,6 @@ struct QCfg {
   static constexpr int TPITCH = BN + 8;          // transposed image
   static_assert(DSPLIT == 1 || QSUB == 1, "head-dim split assumes one row subtile per wave");
 };
-
-// ---------------------------------------------------------------------------------------------
-// block decode + KV tile schedule shared by fwd and dq
-// ---------------------------------------------------------------------------------------------
-struct QBlock {
-  int hk, hc, mb, seq, row_begin, R, blk_row0;
-  int c0, n_ctx, d0, n_dec, n_tiles;
-};
-
-template <int BN>
-__device__ __forceinline__ bool decode_qblock(const AttnParams& p, QBlock& b) {
-  int t = blockIdx.x;
-  b.hk = t % p.Hk; t /= p.Hk;
-  b.hc = t % p.HC; t /= p.HC;
-  b.mb = p.MB - 1 - (t % p.MB);   // late (long-horizon) row blocks first
-  b.seq = t / p.MB;
-  b.row_begin = p.cu ? p.cu[b.seq] : 0;
-  b.R = p.cu ? (p.cu[b.seq + 1] - b.row_begin) : p.total;
-  b.blk_row0 = b.mb * p.BMR;
-  if (b.blk_row0 >= b.R) return false;
-  const int P = p.ctx_len;
-  const int last_row = min(b.R, b.blk_row0 + p.BMR) - 1;
-  b.n_ctx = (P + BN - 1) / BN;
-  b.n_dec = last_row / BN + 1;
-  b.c0 = 0;
-  b.d0 = 0;
-  if (p.window > 0) {
-    // lowest key any row of the block may see: logical (P + blk_row0) - W + 1
-    const int lo = P + b.blk_row0 - p.window + 1;
-    if (lo >= P) {
-      b.c0 = b.n_ctx;
-      b.d0 = (lo - P) / BN;
-    } else if (lo > 0) {
-      b.c0 = lo / BN;
-    }
-  }
-  b.n_tiles = (b.n_ctx - b.c0) + (b.n_dec - b.d0);
-  return true;
-}
-
-// Visibility of key `key` (index inside its region) for row `row` of the sequence.
-template <bool LOCAL>
-__device__ __forceinline__ bool visible(bool is_ctx, int key, int row, int P, int R, int W) {
-  if (is_ctx) {
-    bool ok = key < P;
-    if (LOCAL) ok = ok && (key > P + row - W);
-    return ok;
-  }
-  bool ok = (key <= row) && (key < R);
-  if (LOCAL) ok = ok && (key > row - W);
-  return ok;
-}
-
-// Does any (row, key) pair of a 32-row subtile x BN-key tile need masking?
-template <bool LOCAL, int BN>
-__device__ __forceinline__ bool tile_needs_mask(bool is_ctx, int key0, int row0, int P, int R, int W) {
-  if (is_ctx) {
-    bool need = key0 + BN > P;
-    if (LOCAL) need = need || (key0 <= P + row0 + 31 - W);
-    return need;
-  }
-  bool need = (key0 + BN - 1 > row0) || (key0 + BN > R);
-  if (LOCAL) need = need || (key0 <= row0 + 31 - W);
-  return need;
-}
-
-// Is any pair of rows [rmin, rmax] x the BN-key tile visible at all?
-template <bool LOCAL, int BN>
-__device__ __forceinline__ bool tile_active(bool is_ctx, int key0, int rmin, int rmax, int P, int W) {
-  if (is_ctx) {
-    if (LOCAL) return key0 + BN - 1 > P + rmin - W;
-    return true;
-  }
-  bool act = key0 <= rmax;
-  if (LOCAL) act = act && (key0 + BN - 1 > rmin - W);
-  return act;
-}
 
 // ---------------------------------------------------------------------------------------------
 // forward
@@ -532,28 +456,10 @@ __global__ __launch_bounds__(256) void dq_kernel(const AttnParams p) {
 // ---------------------------------------------------------------------------------------------
 // host launchers
 // ---------------------------------------------------------------------------------------------
-static int gcd_int(int a, int b) {
-  while (b) {
-    int t = a % b;
-    a = b;
-    b = t;
-  }
-  return a;
-}
-
-template <int NST>
-static void fill_packing(AttnParams& p) {
-  p.GP = gcd_int(p.G, NST);
-  p.RSH = NST / p.GP;
-  p.BMR = p.RSH * 32;
-  p.HC = p.G / p.GP;
-  p.MB = (p.max_rows + p.BMR - 1) / p.BMR;
-}
-
 template <int D, int DSPLIT, int QSUB, int BN, bool LOCAL>
 static hipError_t launch_fwd_t(AttnParams p, hipStream_t st) {
   using C = QCfg<D, DSPLIT, QSUB, BN>;
-  fill_packing<C::NST>(p);
+  fill_packing(p, C::NST);
   size_t smem = (size_t)(BN * C::KPITCH + D * C::TPITCH) * 2;
   if (DSPLIT > 1) smem += (size_t)C::NW * C::KVSUB * 16 * 64 * 4;
   auto kern = fwd_kernel<D, DSPLIT, QSUB, BN, LOCAL>;
@@ -569,7 +475,7 @@ static hipError_t launch_fwd_t(AttnParams p, hipStream_t st) {
 template <int D, int DSPLIT, int QSUB, int BN, bool LOCAL>
 static hipError_t launch_dq_t(AttnParams p, hipStream_t st) {
   using C = QCfg<D, DSPLIT, QSUB, BN>;
-  fill_packing<C::NST>(p);
+  fill_packing(p, C::NST);
   size_t smem = (size_t)(2 * BN * C::KPITCH + D * C::TPITCH) * 2;
   if (DSPLIT > 1) smem += (size_t)2 * C::NW * C::KVSUB * 16 * 64 * 4;
   auto kern = dq_kernel<D, DSPLIT, QSUB, BN, LOCAL>;
