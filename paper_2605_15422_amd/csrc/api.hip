@@ -95,6 +95,14 @@ hipError_t run_fwd(const AttnParams& p, int d, hipStream_t st) {
   if (d <= 128) return dkv::launch_fwd2(p, d, st);
   return dkv::launch_fwd(p, d, st);
 }
+hipError_t run_dq(const AttnParams& p, int d, hipStream_t st) {
+  if (d <= 128) return dkv::launch_dq2(p, d, st);
+  return dkv::launch_dq(p, d, st);
+}
+hipError_t run_dkdv(const AttnParams& p, int d, hipStream_t st) {
+  if (d <= 128) return dkv::launch_dkdv2(p, d, st);
+  return dkv::launch_dkdv(p, d, st);
+}
 
 void base_params(AttnParams& p, const dualkv_shape* s) {
   p = AttnParams{};
@@ -249,8 +257,8 @@ int dualkv_ctx_bwd(const dualkv_shape* shape, dualkv_tin do_c, dualkv_tin o_c, c
   const bool do_dq = !(shape->flags & DUALKV_FLAG_SKIP_DQ), do_dkdv = !(shape->flags & DUALKV_FLAG_SKIP_DKDV);
   if (!(shape->flags & DUALKV_FLAG_SKIP_PRE) && (rc = hip_rc(dkv::launch_dot_do_o(p.dout, p.o, p.dvec, P, p.H, d, st))))
     return rc;
-  if (do_dkdv && (rc = hip_rc(dkv::launch_dkdv(p, d, st)))) return rc;
-  if (do_dq) return hip_rc(dkv::launch_dq(p, d, st));
+  if (do_dkdv && (rc = hip_rc(run_dkdv(p, d, st)))) return rc;
+  if (do_dq) return hip_rc(run_dq(p, d, st));
   return DUALKV_OK;
 }
 
@@ -326,13 +334,13 @@ int dualkv_bwd(const dualkv_shape* shape, dualkv_tin do_d, dualkv_tin o_d, const
   if (T > 0 && !(shape->flags & DUALKV_FLAG_SKIP_PRE) &&
       (rc = hip_rc(dkv::launch_dot_do_o(p.dout, p.o, p.dvec, T, p.H, d, st))))
     return rc;
-  if (do_dkdv && (rc = hip_rc(dkv::launch_dkdv(p, d, st)))) return rc;
+  if (do_dkdv && (rc = hip_rc(run_dkdv(p, d, st)))) return rc;
   if (scratch && do_dkdv) {
     // Stage 2 (Alg. 2): cast the accumulated prompt gradients once
     if ((rc = hip_rc(dkv::launch_convert_ctx(p.dkc_acc, view(dk_c), P, p.Hk, d, 1.0f, st)))) return rc;
     if ((rc = hip_rc(dkv::launch_convert_ctx(p.dvc_acc, view(dv_c), P, p.Hk, d, 1.0f, st)))) return rc;
   }
-  if (T > 0 && do_dq) return hip_rc(dkv::launch_dq(p, d, st));
+  if (T > 0 && do_dq) return hip_rc(run_dq(p, d, st));
   return DUALKV_OK;
 }
 

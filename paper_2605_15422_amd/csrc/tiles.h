@@ -1,0 +1,58 @@
+// Un-padded, XOR-swizzled LDS tiles for head dims 64 / 128 and the LDS transpose read.
+//
+// A tile is ROWS x D bf16, row-major, 2*D bytes per row, made of 16-byte chunks.  Chunk c of row r is
+// stored at chunk position c ^ swz<D>(r).  The swizzle makes all three access patterns used by the
+// kernels bank-conflict free on the 64-bank LDS:
+//   * 16-byte staging writes (16 lanes = consecutive chunks of a row),
+//   * 16-byte MFMA operand reads with the lane on the row axis (16 lanes = 16 consecutive rows, same
+//     chunk),
+//   * ds_read_b64_tr_b16 transpose reads with the lane on the column axis (16 lanes = 4 consecutive
+//     rows x 32 contiguous bytes; the neighbouring 16 lanes read the next 32 bytes of the same rows).
+//
+// ds_read_b64_tr_b16: within each group of 16 lanes, lane i supplies the address of 4 consecutive
+// 16-bit values; viewing the 16 x 4 values as a flat list v[0..63] (lane-major), lane i receives
+// v[i], v[16+i], v[32+i], v[48+i].  With lane i pointing at row k0 + i/4, columns d0 + 4*(i%4) .. +3 of
+// a row-major tile, lane i therefore receives column d0 + i of rows k0 .. k0+3: a K-indexed MFMA
+// operand of the transposed tile without any transposed copy in LDS.
+#pragma once
+#include "common.h"
+
+namespace dkv {
+
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+
+template <int D>
+__device__ __forceinline__ int swz(int row) {
+  static_assert(D == 64 || D == 128, "swizzle defined for 64 / 128");
+  if (D == 128) return ((row & 3) << 2) | ((row >> 2) & 3);
+  return (((row >> 1) & 1) << 2) | ((row >> 2) & 3);
+}
+
+// byte offset of chunk `chunk` of row `row` inside a tile
+template <int D>
+__device__ __forceinline__ int tile_off(int row, int chunk) {
+  return row * (2 * D) + ((chunk ^ swz<D>(row)) << 4);
+}
+
+// Per-lane byte offset for a transpose read of rows (row_base + (lane%16)/4), columns
+// col_base + 16*((lane/16)%2) + 4*(lane%4) .. +3, where row_base is a multiple of 4 given relative to a
+// 16-row aligned origin (the swizzle has period 16 rows).
+template <int D>
+__device__ __forceinline__ int tr_off(int lane, int row_base, int col_base) {
+  const int r16 = lane & 15, g = (lane >> 4) & 1;
+  const int row = row_base + (r16 >> 2);
+  const int col = col_base + g * 16 + (r16 & 3) * 4;
+  return tile_off<D>(row, col >> 3) + ((col >> 2) & 1) * 8;
+}
+
+// two transpose reads (rows k0..k0+3 and k0+8..k0+11 of the lane's group) -> one MFMA operand
+__device__ __forceinline__ bf16x8 tr_pair(const unsigned char* a0, const unsigned char* a1) {
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(a0));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(a1));
+  const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, v);
+}
+
+}  // namespace dkv
