@@ -100,7 +100,7 @@ hipError_t run_dq(const AttnParams& p, int d, hipStream_t st) {
   return dkv::launch_dq(p, d, st);
 }
 hipError_t run_dkdv(const AttnParams& p, int d, hipStream_t st) {
-  if (d <= 128) return dkv::launch_dkdv2(p, d, st);
+  if (d <= 128) return dkv::launch_dkdv3(p, d, st);
   return dkv::launch_dkdv(p, d, st);
 }
 
