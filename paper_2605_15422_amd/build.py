@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdualkv.so")
-SOURCES = ["api.hip", "qstat.hip", "fwd2.hip", "dq2.hip", "dkdv2.hip", "dkdv3.hip", "kvstat.hip", "aux.hip"]
+SOURCES = ["api.hip", "qstat.hip", "fwd2.hip", "dq2.hip", "dkdv3.hip", "kvstat.hip", "aux.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-munsafe-fp-atomics",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 
@@ -22,6 +22,7 @@ def _hipcc() -> str:
 
 
 def build(verbose: bool = True, extra_flags=()) -> str:
+    extra_flags = tuple(extra_flags) + tuple(os.environ.get("DUALKV_EXTRA_HIPCC_FLAGS", "").split())
     objdir = os.path.join(HERE, "_build")
     os.makedirs(objdir, exist_ok=True)
     hipcc = _hipcc()

@@ -53,8 +53,24 @@ __device__ __forceinline__ bf16x8 pack8_bf16(const float* v) {
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __builtin_bit_cast(float, w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __builtin_bit_cast(float, w & 0xffff0000u); }
 
-__device__ __forceinline__ float xor32_max(float x) { return fmaxf(x, __shfl_xor(x, 32)); }
-__device__ __forceinline__ float xor32_sum(float x) { return x + __shfl_xor(x, 32); }
+// Combine a value with the one held by lane ^ 32.  v_permlane32_swap exchanges, in place, the upper
+// 32 lanes of its first operand with the lower 32 lanes of its second; fed two copies of the same value,
+// every lane ends up with its own value in one register and its partner's in the other (no LDS round
+// trip).  Written as inline asm with both registers as read-write operands; the leading s_nop covers
+// the VALU-write -> permlane-read hazard the compiler cannot see.
+__device__ __forceinline__ void swap32(float& a, float& b) {
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+}
+__device__ __forceinline__ float xor32_max(float x) {
+  float a = x, b = x;
+  swap32(a, b);
+  return fmaxf(a, b);
+}
+__device__ __forceinline__ float xor32_sum(float x) {
+  float a = x, b = x;
+  swap32(a, b);
+  return a + b;
+}
 
 // Row of a C tile held in register r by this lane.
 __device__ __forceinline__ int crow(int r, int hi) { return 8 * (r >> 2) + 4 * hi + (r & 3); }

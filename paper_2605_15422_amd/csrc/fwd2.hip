@@ -13,15 +13,17 @@
 #include "common.h"
 #include "launch.h"
 #include "qsched.h"
+#include "tiles.h"
 
 namespace dkv {
 
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+#ifndef DKV_FWD_NW
+#define DKV_FWD_NW 8
+#endif
 
 template <int D>
 struct F2Cfg {
-  static constexpr int NW = 8, NT = 512, BN = 64;
+  static constexpr int NW = DKV_FWD_NW, NT = NW * 64, BN = 64;
   static constexpr int KS = D / 16, DSUB = D / 32, KVSUB = BN / 32;
   static constexpr int RB = 2 * D;                 // row bytes
   static constexpr int CPR = D / 8;                // 16-byte chunks per row
@@ -34,16 +36,8 @@ struct F2Cfg {
   __device__ static __forceinline__ int fV(int row) { return 4 * ((row / RPL) % (CPR / 4)); }
 };
 
-__device__ __forceinline__ bf16x8 tr_pair(const unsigned char* a0, const unsigned char* a1) {
-  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(a0));
-  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(a1));
-  typedef short s16x8 __attribute__((ext_vector_type(8)));
-  const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-  return __builtin_bit_cast(bf16x8, v);
-}
-
 template <int D, bool LOCAL>
-__global__ __launch_bounds__(512) void fwd2_kernel(const AttnParams p) {
+__global__ __launch_bounds__(DKV_FWD_NW * 64) void fwd2_kernel(const AttnParams p) {
   using C = F2Cfg<D>;
   constexpr int BN = C::BN;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -161,6 +155,14 @@ __global__ __launch_bounds__(512) void fwd2_kernel(const AttnParams p) {
           s[kv] = mfma32(a, qf[ks], s[kv]);
         }
       }
+      // instruction order: keep four K-operand reads in flight ahead of the MFMA that consumes them
+      __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+      for (int i = 0; i < C::KVSUB * C::KS - 4; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
       if (tile_needs_mask<LOCAL, BN>(is_ctx, key0, row0, P, R, W)) {
 #pragma unroll
         for (int kv = 0; kv < C::KVSUB; ++kv)
@@ -237,7 +239,7 @@ __global__ __launch_bounds__(512) void fwd2_kernel(const AttnParams p) {
 template <int D, bool LOCAL>
 static hipError_t launch_fwd2_t(AttnParams p, hipStream_t st) {
   using C = F2Cfg<D>;
-  fill_packing(p, 8);
+  fill_packing(p, C::NW);
   const size_t smem = 4 * C::TILE_BYTES;
   auto kern = fwd2_kernel<D, LOCAL>;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -245,7 +247,7 @@ static hipError_t launch_fwd2_t(AttnParams p, hipStream_t st) {
   if (e != hipSuccess) return e;
   const int64_t nblk = (int64_t)p.n_seqs * p.MB * p.HC * p.Hk;
   if (nblk == 0) return hipSuccess;
-  hipLaunchKernelGGL(kern, dim3((unsigned)nblk), dim3(512), smem, st, p);
+  hipLaunchKernelGGL(kern, dim3((unsigned)nblk), dim3(C::NT), smem, st, p);
   return hipGetLastError();
 }
 
