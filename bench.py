@@ -21,6 +21,16 @@ sys.path.insert(0, ROOT)
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch (read + written) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by the
+# calibration factors derived in profiles/cfg2_qwen8b_hbm_traffic.txt (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0).
+MEASURED_TRAFFIC_BYTES = {
+    ("cfg2_qwen8b", "fwd"): 2 * 230643 * 1024 + 133131 * 1024,
+    ("cfg2_qwen8b", "bwd_dq"): 2 * 297051 * 1024 + 131072 * 1024,
+    ("cfg2_qwen8b", "bwd_dkdv"): 2 * 840403 * 1024 + 99432 * 1024,
+    ("cfg2_qwen8b", "ctx_fwd"): 2 * 72123 * 1024 + 66563 * 1024,
+    ("cfg2_qwen8b", "ctx_bwd_dq"): 2 * 106473 * 1024 + 65536 * 1024,
+    ("cfg2_qwen8b", "ctx_bwd_dkdv"): 2 * 1510670 * 1024 + 32843 * 1024,
+}
 
 
 def _events(n):
@@ -211,7 +221,7 @@ def main():
                     "ctx_bwd_dkdv": "dkdv_kernel (Call 1)", "ctx_bwd_dq": "dq_kernel (Call 1)"}
     roofline = {"bound": "mfma", "kernel": kernel_names[dom], "achieved": round(achieved, 2),
                 "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
-                "traffic": None, "kernel_ms": round(stage[dom], 4),
+                "traffic": MEASURED_TRAFFIC_BYTES.get((args.config, dom)), "kernel_ms": round(stage[dom], 4),
                 "algorithmic_flops_per_launch": kern_flops[dom]}
 
     tflops = fl["layer"] / (ms * 1e-3) / 1e12
