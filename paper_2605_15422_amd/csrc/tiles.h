@@ -55,4 +55,35 @@ __device__ __forceinline__ bf16x8 tr_pair(const unsigned char* a0, const unsigne
   return __builtin_bit_cast(bf16x8, v);
 }
 
+// ---------------------------------------------------------------------------------------------
+// Transposed image of a 64-row tile: image row = column index of the source tile (one per head-dim
+// value), 128 bytes per image row holding the 64 source rows in "kperm" order (within every group of
+// 16 the two middle groups of four are swapped, so the eight contraction indices one MFMA lane needs
+// are one contiguous 16-byte chunk).  16-byte chunk c of image row d sits at chunk position
+// c ^ ((d / 2) % 8): two image rows share a 256-byte bank line, and the swizzle makes the operand reads
+// (16 lanes = 16 consecutive image rows, same chunk) conflict free.  Measured on gfx950, 16-byte reads of
+// such an image sustain about 2.5x the bytes per cycle of ds_read_b64_tr_b16 on a row-major tile, so the
+// kernels pay the transposition once, at staging time, instead of on every operand read.
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ int tt_off(int d, int chunk) { return d * 128 + ((chunk ^ ((d >> 1) & 7)) << 4); }
+
+// Store the 4 x 8 block of source rows 4*rq .. 4*rq+3, columns 8*ch .. 8*ch+7 (one 16-byte load per row,
+// v[0..3]) into the transposed image: eight 8-byte writes.
+__device__ __forceinline__ void store_unit_transposed(unsigned char* img, u32x4 r0, u32x4 r1, u32x4 r2, u32x4 r3,
+                                                      int rq, int ch) {
+  const int pos4 = kperm4(rq);
+  const int coff = (pos4 & 1) * 8;
+#pragma unroll
+  for (int m = 0; m < 4; ++m) {
+    u32x2 lo, hi;
+    lo.x = (r0[m] & 0xffffu) | (r1[m] << 16);
+    lo.y = (r2[m] & 0xffffu) | (r3[m] << 16);
+    hi.x = (r0[m] >> 16) | (r1[m] & 0xffff0000u);
+    hi.y = (r2[m] >> 16) | (r3[m] & 0xffff0000u);
+    const int d0 = ch * 8 + 2 * m;
+    *reinterpret_cast<u32x2*>(img + tt_off(d0, pos4 >> 1) + coff) = lo;
+    *reinterpret_cast<u32x2*>(img + tt_off(d0 + 1, pos4 >> 1) + coff) = hi;
+  }
+}
+
 }  // namespace dkv
