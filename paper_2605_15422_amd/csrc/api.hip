@@ -1,5 +1,6 @@
 // C ABI of the library (include/dualkv.h): host-side validation, workspace carving and dispatch.
 // Nothing here touches device memory except through kernel launches on the caller's stream.
+#include <cstdlib>
 #include "../../include/dualkv.h"
 
 #include "common.h"
@@ -73,7 +74,7 @@ int ctx_split(const dualkv_shape* s) {
 }
 
 struct BwdWorkspace {
-  size_t dvec_off, dvec_bytes, acc_off, acc_bytes, total;
+  size_t dvec_off, dvec_bytes, lse2_off, acc_off, acc_bytes, total;
 };
 
 BwdWorkspace bwd_workspace(const dualkv_shape* s, bool ctx_call) {
@@ -81,11 +82,12 @@ BwdWorkspace bwd_workspace(const dualkv_shape* s, bool ctx_call) {
   const int64_t rows = ctx_call ? s->ctx_len : s->total_resp;
   w.dvec_off = 0;
   w.dvec_bytes = align_up((size_t)rows * s->n_q_heads * sizeof(float), 256);
-  w.acc_off = w.dvec_bytes;
+  w.lse2_off = w.dvec_bytes;
+  w.acc_off = 2 * w.dvec_bytes;
   w.acc_bytes = 0;
   if (!ctx_call && !(s->flags & DUALKV_FLAG_ACCUM_CTX_F32) && ctx_split(s) > 1)
     w.acc_bytes = align_up((size_t)s->ctx_len * s->n_kv_heads * s->head_dim * sizeof(float), 256);
-  w.total = w.dvec_bytes + 2 * w.acc_bytes;
+  w.total = 2 * w.dvec_bytes + 2 * w.acc_bytes;
   return w;
 }
 
@@ -100,7 +102,7 @@ hipError_t run_dq(const AttnParams& p, int d, hipStream_t st) {
   return dkv::launch_dq(p, d, st);
 }
 hipError_t run_dkdv(const AttnParams& p, int d, hipStream_t st) {
-  if (d <= 128) return dkv::launch_dkdv3(p, d, st);
+  if (d <= 128) return getenv("DUALKV_DKDV3") ? dkv::launch_dkdv3(p, d, st) : dkv::launch_dkdv4(p, d, st);
   return dkv::launch_dkdv(p, d, st);
 }
 
@@ -249,13 +251,14 @@ int dualkv_ctx_bwd(const dualkv_shape* shape, dualkv_tin do_c, dualkv_tin o_c, c
   }
   p.lse = const_cast<float*>(lse_c);
   p.dvec = reinterpret_cast<float*>(static_cast<char*>(workspace) + w.dvec_off);
+  p.lse2 = reinterpret_cast<float*>(static_cast<char*>(workspace) + w.lse2_off);
   p.cu = nullptr;
   p.n_seqs = 1;
   p.ctx_len = 0;
   p.total = P;
   p.max_rows = P;
   const bool do_dq = !(shape->flags & DUALKV_FLAG_SKIP_DQ), do_dkdv = !(shape->flags & DUALKV_FLAG_SKIP_DKDV);
-  if (!(shape->flags & DUALKV_FLAG_SKIP_PRE) && (rc = hip_rc(dkv::launch_dot_do_o(p.dout, p.o, p.dvec, P, p.H, d, st))))
+  if (!(shape->flags & DUALKV_FLAG_SKIP_PRE) && (rc = hip_rc(dkv::launch_dot_do_o(p.dout, p.o, p.lse, p.dvec, p.lse2, P, p.H, d, st))))
     return rc;
   if (do_dkdv && (rc = hip_rc(run_dkdv(p, d, st)))) return rc;
   if (do_dq) return hip_rc(run_dq(p, d, st));
@@ -306,6 +309,7 @@ int dualkv_bwd(const dualkv_shape* shape, dualkv_tin do_d, dualkv_tin o_d, const
   p.dvd = view(dv_d);
   p.lse = const_cast<float*>(lse_d);
   p.dvec = reinterpret_cast<float*>(static_cast<char*>(workspace) + w.dvec_off);
+  p.lse2 = reinterpret_cast<float*>(static_cast<char*>(workspace) + w.lse2_off);
   p.cu = cu_seqlens_dev;
   p.n_seqs = shape->n_seqs;
   p.ctx_len = P;
@@ -332,7 +336,7 @@ int dualkv_bwd(const dualkv_shape* shape, dualkv_tin do_d, dualkv_tin o_d, const
   }
   const bool do_dq = !(shape->flags & DUALKV_FLAG_SKIP_DQ), do_dkdv = !(shape->flags & DUALKV_FLAG_SKIP_DKDV);
   if (T > 0 && !(shape->flags & DUALKV_FLAG_SKIP_PRE) &&
-      (rc = hip_rc(dkv::launch_dot_do_o(p.dout, p.o, p.dvec, T, p.H, d, st))))
+      (rc = hip_rc(dkv::launch_dot_do_o(p.dout, p.o, p.lse, p.dvec, p.lse2, T, p.H, d, st))))
     return rc;
   if (do_dkdv && (rc = hip_rc(run_dkdv(p, d, st)))) return rc;
   if (scratch && do_dkdv) {

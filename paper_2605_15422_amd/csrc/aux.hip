@@ -11,8 +11,9 @@ namespace dkv {
 // 16 bytes of dO and of O, so a wave reads whole contiguous rows.
 // ---------------------------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(256) void dot_do_o_kernel(TView dout, TView o, float* __restrict__ dvec, int total,
-                                                       int H) {
+__global__ __launch_bounds__(256) void dot_do_o_kernel(TView dout, TView o, const float* __restrict__ lse,
+                                                       float* __restrict__ dvec, float* __restrict__ lse2,
+                                                       int total, int H) {
   constexpr int LPR = D / 8;          // lanes per (row, head)
   constexpr int RPB = 256 / LPR;      // (row, head) pairs per block
   const int tid = threadIdx.x;
@@ -32,20 +33,23 @@ __global__ __launch_bounds__(256) void dot_do_o_kernel(TView dout, TView o, floa
   }
 #pragma unroll
   for (int off = LPR / 2; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
-  if (ok && sub == 0) dvec[(int64_t)h * total + row] = acc;
+  if (ok && sub == 0) {
+    dvec[(int64_t)h * total + row] = acc;
+    lse2[(int64_t)h * total + row] = lse[(int64_t)h * total + row] * LOG2E;   // exponent offset in base-2 units
+  }
 }
 
-hipError_t launch_dot_do_o(const TView& dout, const TView& o, float* dvec, int total, int H, int head_dim,
-                           hipStream_t st) {
+hipError_t launch_dot_do_o(const TView& dout, const TView& o, const float* lse, float* dvec, float* lse2, int total,
+                           int H, int head_dim, hipStream_t st) {
   const int64_t pairs = (int64_t)total * H;
   if (pairs == 0) return hipSuccess;
   const int lpr = head_dim / 8, rpb = 256 / lpr;
   const unsigned grid = (unsigned)((pairs + rpb - 1) / rpb);
   switch (head_dim) {
-    case 64:  hipLaunchKernelGGL(dot_do_o_kernel<64>, dim3(grid), dim3(256), 0, st, dout, o, dvec, total, H); break;
-    case 128: hipLaunchKernelGGL(dot_do_o_kernel<128>, dim3(grid), dim3(256), 0, st, dout, o, dvec, total, H); break;
-    case 256: hipLaunchKernelGGL(dot_do_o_kernel<256>, dim3(grid), dim3(256), 0, st, dout, o, dvec, total, H); break;
-    case 512: hipLaunchKernelGGL(dot_do_o_kernel<512>, dim3(grid), dim3(256), 0, st, dout, o, dvec, total, H); break;
+    case 64:  hipLaunchKernelGGL(dot_do_o_kernel<64>, dim3(grid), dim3(256), 0, st, dout, o, lse, dvec, lse2, total, H); break;
+    case 128: hipLaunchKernelGGL(dot_do_o_kernel<128>, dim3(grid), dim3(256), 0, st, dout, o, lse, dvec, lse2, total, H); break;
+    case 256: hipLaunchKernelGGL(dot_do_o_kernel<256>, dim3(grid), dim3(256), 0, st, dout, o, lse, dvec, lse2, total, H); break;
+    case 512: hipLaunchKernelGGL(dot_do_o_kernel<512>, dim3(grid), dim3(256), 0, st, dout, o, lse, dvec, lse2, total, H); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();

@@ -168,6 +168,7 @@ struct AttnParams {
   TViewOut dq, dkc, dvc, dkd, dvd;       // bwd outputs (bf16)
   float* lse;                            // (H, total) fwd: written, bwd: read
   float* dvec;                           // (H, total) D = rowsum(dO * O), bwd only
+  float* lse2;                           // (H, total) LSE * log2(e), written with D by the preprocess
   float* dkc_acc;                        // optional fp32 (P, Hk, d) accumulators (atomic adds)
   float* dvc_acc;
   float* dkd_acc;                        // optional fp32 (rows, Hk, d) accumulators for response-region keys
@@ -183,6 +184,7 @@ struct AttnParams {
   // KV-stationary kernel
   int n_ctx_tiles, n_dec_tiles;          // per sequence upper bound for dec
   int n_split;                           // ctx tiles: the sequence loop is cut in n_split parts
+  int dbg;
 };
 
 }  // namespace dkv
