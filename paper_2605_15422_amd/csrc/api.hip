@@ -102,7 +102,11 @@ hipError_t run_dq(const AttnParams& p, int d, hipStream_t st) {
   return dkv::launch_dq(p, d, st);
 }
 hipError_t run_dkdv(const AttnParams& p, int d, hipStream_t st) {
-  if (d <= 128) return getenv("DUALKV_DKDV3") ? dkv::launch_dkdv3(p, d, st) : dkv::launch_dkdv4(p, d, st);
+  if (d <= 128) {
+    // the producer/consumer kernel needs the two statistics arrays within 4 GB of each other
+    const bool near = reinterpret_cast<uintptr_t>(p.lse2) - reinterpret_cast<uintptr_t>(p.dvec) < (1ull << 32);
+    return near ? dkv::launch_dkdv4(p, d, st) : dkv::launch_dkdv3(p, d, st);
+  }
   return dkv::launch_dkdv(p, d, st);
 }
 

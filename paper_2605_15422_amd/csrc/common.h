@@ -184,7 +184,6 @@ struct AttnParams {
   // KV-stationary kernel
   int n_ctx_tiles, n_dec_tiles;          // per sequence upper bound for dec
   int n_split;                           // ctx tiles: the sequence loop is cut in n_split parts
-  int dbg;
 };
 
 }  // namespace dkv
