@@ -214,6 +214,7 @@ __global__ __launch_bounds__(512) void dkdv4_kernel(const AttnParams p) {
         bf16x8 dofr[KS];
         load_stat(Uc, 1, dinit);   // their latency hides behind the S chain
         load_frags(Uc, IC<1>{}, dofr);
+        __builtin_amdgcn_sched_barrier(0);   // all reads requested before the first MFMA, not trickled in between
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[r] = 0.f;
 #pragma unroll
@@ -467,15 +468,25 @@ __global__ __launch_bounds__(512) void dkdv4_kernel(const AttnParams p) {
       issue_block(IC<IS>{});
       if (vbits & (1u << (AHEAD + 1))) {
         const unsigned char* xr = xr_lane + XB * XCH_BYTES;
+        // all P / -dS operands are requested before the first MFMA (left alone, the compiler reads one operand,
+        // waits for it and issues one MFMA, sixteen LDS latencies in a row)
+        bf16x8 pa[2][NK], dsa[2][NK];
 #pragma unroll
         for (int t2 = 0; t2 < 2; ++t2)
 #pragma unroll
           for (int i = 0; i < NK; ++i) {
-            const bf16x8 pa = *reinterpret_cast<const bf16x8*>(xr + i * 4096 + t2 * 1024);
-            const bf16x8 dsa = *reinterpret_cast<const bf16x8*>(xr + i * 4096 + (2 + t2) * 1024);
-            dv[i] = mfma32(pa, tdo[t2], dv[i]);
-            dk[i] = mfma32(dsa, tq[t2], dk[i]);
+            pa[t2][i] = *reinterpret_cast<const bf16x8*>(xr + i * 4096 + t2 * 1024);
+            dsa[t2][i] = *reinterpret_cast<const bf16x8*>(xr + i * 4096 + (2 + t2) * 1024);
           }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+          for (int i = 0; i < NK; ++i) {
+            dv[i] = mfma32(pa[t2][i], tdo[t2], dv[i]);
+            dk[i] = mfma32(dsa[t2][i], tq[t2], dk[i]);
+          }
+        __builtin_amdgcn_sched_barrier(0);
       }
       const bool cur = vbits & (1u << AHEAD);
       if (__builtin_expect(cur, 1)) {

@@ -142,14 +142,18 @@ __global__ __launch_bounds__(512) void dq2_kernel(const AttnParams p) {
       }
       const bool need = tile_needs_mask<LOCAL, 32>(is_ctx, key0, row0, P, R, W);
       float dsv[16];
+      // two straight-line variants: a per-element test of a run-time flag costs three branches per element
+      if (__builtin_expect(need, 0)) {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float e = __builtin_amdgcn_exp2f(s[r] * c - lse2);
-        if (need) {
+        for (int r = 0; r < 16; ++r) {
+          float e = __builtin_amdgcn_exp2f(s[r] * c - lse2);
           const int key = key0 + crow(r, hi);
           if (!visible<LOCAL>(is_ctx, key, row, P, R, W)) e = 0.f;
+          dsv[r] = e * (dpt[r] - dvec);   // dS^T
         }
-        dsv[r] = e * (dpt[r] - dvec);   // dS^T
+      } else {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) dsv[r] = __builtin_amdgcn_exp2f(s[r] * c - lse2) * (dpt[r] - dvec);
       }
       // dQ^T += K^T dS^T
 #pragma unroll
