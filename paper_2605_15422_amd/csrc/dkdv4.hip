@@ -25,36 +25,11 @@
 // load is issued inside the main loop (a compiler-placed wait would also wait for all blocks in flight).
 #include <type_traits>
 #include "common.h"
+#include "dma.h"
 #include "launch.h"
 #include "tiles.h"
 
 namespace dkv {
-
-// 64 lanes x 16 bytes: global address = sbase + voff (per lane), LDS address = lds_addr + 16 * lane.
-__device__ __forceinline__ void dma16(const void* sbase, uint32_t voff, uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-               :
-               : "s"(lds_addr), "v"(voff), "s"(sbase)
-               : "memory");
-}
-// 64 lanes x 4 bytes: global address = sbase + voff (per lane), LDS address = lds_addr + 4 * lane.
-__device__ __forceinline__ void dma4(const void* sbase, uint32_t voff, uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
-               :
-               : "s"(lds_addr), "v"(voff), "s"(sbase)
-               : "memory");
-}
-template <int N>
-__device__ __forceinline__ void wait_vm() {
-  asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
-}
-
-__device__ __forceinline__ const u16* uniform_ptr(const u16* ptr) {
-  const uint64_t v = reinterpret_cast<uint64_t>(ptr);
-  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
-  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
-  return reinterpret_cast<const u16*>(((uint64_t)hi << 32) | lo);
-}
 
 enum : int { HDR_VALID = 1, HDR_ACTIVE = 2, HDR_MASK = 4 };
 template <int V>

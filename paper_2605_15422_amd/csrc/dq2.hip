@@ -4,11 +4,13 @@
 // dQ is accumulated in registers and written once: no fp32 dQ scratch, no atomics, no convert pass.
 //
 // Shape: 8 waves (two per SIMD), each owning one 32-row subtile with Q, dO fragments and the dQ^T
-// accumulator in registers; K and V tiles of 64 keys double-buffered in swizzled LDS.  S^T = K Q^T and
+// accumulator in registers; K and V tiles of 64 keys travel global -> LDS directly (global_load_lds, three
+// stages, two tiles ahead: no staging registers, which pays for a deeper operand prefetch) into swizzled LDS.  S^T = K Q^T and
 // dP^T = V dO^T take 16-byte row operands from LDS; dQ^T += K^T dS^T takes K^T through LDS transpose
 // reads of the same row-major K tile.  A 64-key tile is consumed as two 32-key halves so only one
 // 32x32 S and dP tile is live at a time.
 #include "common.h"
+#include "dma.h"
 #include "launch.h"
 #include "qsched.h"
 #include "tiles.h"
@@ -19,12 +21,16 @@ template <int D, bool LOCAL>
 __global__ __launch_bounds__(512) void dq2_kernel(const AttnParams p) {
   constexpr int NT = 512, BN = 64;
   constexpr int KS = D / 16, DSUB = D / 32, RB = 2 * D, CPR = D / 8;
-  constexpr int TILE_BYTES = BN * RB, CPT = BN * CPR / NT;
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];   // [2][K tile | V tile]
+  constexpr int TILE_BYTES = BN * RB;
+  constexpr int NSTAGE = 3, STAGE_BYTES = 2 * TILE_BYTES;
+  constexpr int IPT = TILE_BYTES / 1024 / 8;   // 1 KB load instructions per wave, tile and tensor
+  constexpr int RPI = 1024 / RB;               // rows per load instruction
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];   // [NSTAGE][K tile | V tile]
 
   QBlock b;
   if (!decode_qblock<BN>(p, b)) return;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, hi = lane >> 5;
   const int P = p.ctx_len, R = b.R, W = p.window;
   const float c = p.scale_log2;
@@ -47,6 +53,10 @@ __global__ __launch_bounds__(512) void dq2_kernel(const AttnParams p) {
     }
     lse2 = p.lse[(int64_t)head * p.total + grow] * LOG2E;
     dvec = p.dvec[(int64_t)head * p.total + grow];
+    // consumed (and therefore waited for) here: no compiler-placed vector-memory wait inside the main loop
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) asm volatile("" : : "v"(qf[ks]), "v"(dof[ks]));
+    asm volatile("" : : "v"(lse2), "v"(dvec));
   }
 
   f32x16 dqacc[DSUB];
@@ -71,52 +81,46 @@ __global__ __launch_bounds__(512) void dq2_kernel(const AttnParams p) {
   const u16* kd_base = p.kd.ptr + (int64_t)b.row_begin * p.kd.ts + (int64_t)b.hk * p.kd.hs;
   const u16* vd_base = p.vd.ptr + (int64_t)b.row_begin * p.vd.ts + (int64_t)b.hk * p.vd.hs;
   const int n_ctx_run = b.n_ctx - b.c0;
-  int st_row[CPT], st_col[CPT], st_off[CPT];
-#pragma unroll
-  for (int j = 0; j < CPT; ++j) {
-    const int id = tid + j * NT;
-    st_row[j] = id / CPR;
-    st_col[j] = (id % CPR) * 8;
-    st_off[j] = tile_off<D>(st_row[j], id % CPR);
-  }
-  u32x4 kst[CPT], vst[CPT];
-  auto issue_loads = [&](int it) {
+  // global -> LDS tile loads: instruction j = wave + 8 t of a tile covers RPI key rows; lane l lands at LDS
+  // chunk position l % CPR of row l / CPR of the instruction and fetches the chunk the swizzle stores there
+  // (the swizzle has period 16 rows, so one offset serves every t).  Keys past the end of the region re-read
+  // the last key: their scores are masked like any invisible key.
+  const uint32_t smem_addr = (uint32_t)reinterpret_cast<uintptr_t>(smem);
+  const int ld_row0 = wave * RPI + lane / CPR;
+  const int ld_coff = ((lane % CPR) ^ swz<D>(ld_row0)) * 16;
+  auto issue_loads = [&](int it, int stage) __attribute__((always_inline)) {
     const bool is_ctx = it < n_ctx_run;
     const int key0 = is_ctx ? (b.c0 + it) * BN : (b.d0 + it - n_ctx_run) * BN;
-    const u16* kb = is_ctx ? kc_base : kd_base;
-    const u16* vb = is_ctx ? vc_base : vd_base;
-    const int64_t kts = is_ctx ? p.kc.ts : p.kd.ts, vts = is_ctx ? p.vc.ts : p.vd.ts;
-    const int nvalid = (is_ctx ? P : R) - key0;
+    const int kts = (int)(is_ctx ? p.kc.ts : p.kd.ts), vts = (int)(is_ctx ? p.vc.ts : p.vd.ts);
+    const u16* kb = uniform_ptr((is_ctx ? kc_base : kd_base) + (int64_t)key0 * kts);
+    const u16* vb = uniform_ptr((is_ctx ? vc_base : vd_base) + (int64_t)key0 * vts);
+    const int last = (is_ctx ? P : R) - key0 - 1;
+    const uint32_t dst = smem_addr + stage * STAGE_BYTES + wave * 1024;
 #pragma unroll
-    for (int j = 0; j < CPT; ++j) {
-      u32x4 zk = {0u, 0u, 0u, 0u}, zv = {0u, 0u, 0u, 0u};
-      if (st_row[j] < nvalid) {
-        zk = *reinterpret_cast<const u32x4*>(kb + (int64_t)(key0 + st_row[j]) * kts + st_col[j]);
-        zv = *reinterpret_cast<const u32x4*>(vb + (int64_t)(key0 + st_row[j]) * vts + st_col[j]);
-      }
-      kst[j] = zk;
-      vst[j] = zv;
+    for (int t = 0; t < IPT; ++t) {
+      const int row = min(ld_row0 + t * 8 * RPI, last);
+      dma16(kb, (uint32_t)(row * kts * 2 + ld_coff), dst + t * 8192);
+      dma16(vb, (uint32_t)(row * vts * 2 + ld_coff), dst + TILE_BYTES + t * 8192);
     }
   };
-  auto store_stage = [&](int buf) {
-    unsigned char* kb = smem + buf * 2 * TILE_BYTES;
-#pragma unroll
-    for (int j = 0; j < CPT; ++j) {
-      *reinterpret_cast<u32x4*>(kb + st_off[j]) = kst[j];
-      *reinterpret_cast<u32x4*>(kb + TILE_BYTES + st_off[j]) = vst[j];
-    }
+  // the tile consumed next must have landed; the 2 IPT loads of the tile after it may stay in flight
+  auto wait_loads = [&](bool newer_in_flight) __attribute__((always_inline)) {
+    wait_vm<2 * IPT>();
+    if (__builtin_expect(!newer_in_flight, 0)) wait_vm<0>();
   };
 
-  issue_loads(0);
-  store_stage(0);
-  if (b.n_tiles > 1) issue_loads(1);
+  issue_loads(0, 0);
+  if (b.n_tiles > 1) issue_loads(1, 1);
+  wait_loads(b.n_tiles > 1);
   __syncthreads();
 
+  int stage = 0;
   for (int it = 0; it < b.n_tiles; ++it) {
-    if (it + 1 < b.n_tiles) store_stage((it + 1) & 1);
-    if (it + 2 < b.n_tiles) issue_loads(it + 2);
+    // tile it+2 goes into the stage that tile it-1 left at the last barrier
+    const int stage2 = stage == 0 ? 2 : stage - 1;
+    if (it + 2 < b.n_tiles) issue_loads(it + 2, stage2);
 
-    const unsigned char* Kb = smem + (it & 1) * 2 * TILE_BYTES;
+    const unsigned char* Kb = smem + stage * STAGE_BYTES;
     const unsigned char* Vb = Kb + TILE_BYTES;
     const bool is_ctx = it < n_ctx_run;
     const int tile_key0 = is_ctx ? (b.c0 + it) * BN : (b.d0 + it - n_ctx_run) * BN;
@@ -140,6 +144,15 @@ __global__ __launch_bounds__(512) void dq2_kernel(const AttnParams p) {
         s = mfma32(*reinterpret_cast<const bf16x8*>(kh + roff[ks]), qf[ks], s);
         dpt = mfma32(*reinterpret_cast<const bf16x8*>(vh + roff[ks]), dof[ks], dpt);
       }
+      // instruction order: keep four operand reads in flight ahead of the MFMA that consumes them (left alone,
+      // the compiler reads two operands, waits for them and issues two MFMAs: one LDS latency per pair)
+      __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+      for (int i = 0; i < 2 * KS - 4; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
       const bool need = tile_needs_mask<LOCAL, 32>(is_ctx, key0, row0, P, R, W);
       float dsv[16];
       // two straight-line variants: a per-element test of a run-time flag costs three branches per element
@@ -165,7 +178,9 @@ __global__ __launch_bounds__(512) void dq2_kernel(const AttnParams p) {
           dqacc[ds] = mfma32(tr_pair(kt + toff0[ds], kt + toff1[ds]), pb, dqacc[ds]);
       }
     }
+    wait_loads(it + 2 < b.n_tiles);
     __syncthreads();
+    stage = stage == 2 ? 0 : stage + 1;
   }
 
   if (row < R) {
@@ -185,7 +200,7 @@ __global__ __launch_bounds__(512) void dq2_kernel(const AttnParams p) {
 template <int D, bool LOCAL>
 static hipError_t launch_dq2_t(AttnParams p, hipStream_t st) {
   fill_packing(p, 8);
-  const size_t smem = 4 * 64 * 2 * D;
+  const size_t smem = 3 * 2 * 64 * 2 * D;
   auto kern = dq2_kernel<D, LOCAL>;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);

@@ -8,9 +8,10 @@
 //   * K and V tiles (64 keys) are staged row-major, un-padded, XOR-swizzled by row so that both the
 //     16-byte K operand reads and the transposing V reads are bank-conflict free; V^T operands come
 //     from ds_read_b64_tr_b16 (LDS transpose read), so nothing is transposed on the way into LDS;
-//   * LDS is double-buffered: global loads for tile t+2 are in flight and tile t+1 is written to the
-//     other buffer while tile t is consumed; one barrier per tile.
+//   * the tiles travel global -> LDS directly (global_load_lds, three stages, two tiles ahead): no
+//     staging registers, no LDS stores, one barrier per tile.
 #include "common.h"
+#include "dma.h"
 #include "launch.h"
 #include "qsched.h"
 #include "tiles.h"
@@ -44,7 +45,8 @@ __global__ __launch_bounds__(DKV_FWD_NW * 64) void fwd2_kernel(const AttnParams 
   // [2][K tile | V tile]
   QBlock b;
   if (!decode_qblock<BN>(p, b)) return;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, hi = lane >> 5;
   const int P = p.ctx_len, R = b.R, W = p.window;
   const float c = p.scale_log2;
@@ -60,6 +62,9 @@ __global__ __launch_bounds__(DKV_FWD_NW * 64) void fwd2_kernel(const AttnParams 
     const u16* qp = p.q.ptr + (int64_t)(b.row_begin + r) * p.q.ts + (int64_t)head * p.q.hs + hi * 8;
 #pragma unroll
     for (int ks = 0; ks < C::KS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16);
+    // consumed (and therefore waited for) here: no compiler-placed vector-memory wait inside the main loop
+#pragma unroll
+    for (int ks = 0; ks < C::KS; ++ks) asm volatile("" : : "v"(qf[ks]));
   }
 
   f32x16 oacc[C::DSUB];
@@ -84,60 +89,55 @@ __global__ __launch_bounds__(DKV_FWD_NW * 64) void fwd2_kernel(const AttnParams 
     }
   }
 
-  // ---- staging: thread -> CPT chunks of K and of V
+  // ---- global -> LDS tile loads: instruction j = wave + 8 t of a tile covers RPI key rows; lane l lands at
+  // LDS chunk position l % CPR of row l / CPR of the instruction and fetches the chunk the swizzle stores
+  // there (both swizzles have a period that divides 8 RPI rows, so one offset per tensor serves every t).
+  // Keys past the end of the region re-read the last key: their scores are masked like any invisible key.
   const u16* kc_base = p.kc.ptr + (int64_t)b.hk * p.kc.hs;
   const u16* vc_base = p.vc.ptr + (int64_t)b.hk * p.vc.hs;
   const u16* kd_base = p.kd.ptr + (int64_t)b.row_begin * p.kd.ts + (int64_t)b.hk * p.kd.hs;
   const u16* vd_base = p.vd.ptr + (int64_t)b.row_begin * p.vd.ts + (int64_t)b.hk * p.vd.hs;
   const int n_ctx_run = b.n_ctx - b.c0;
-  int st_row[C::CPT], st_col[C::CPT], st_koff[C::CPT], st_voff[C::CPT];
-#pragma unroll
-  for (int j = 0; j < C::CPT; ++j) {
-    const int id = tid + j * C::NT;
-    st_row[j] = id / C::CPR;
-    st_col[j] = (id % C::CPR) * 8;
-    st_koff[j] = st_row[j] * C::RB + (((id % C::CPR) ^ C::fK(st_row[j])) << 4);
-    st_voff[j] = st_row[j] * C::RB + (((id % C::CPR) ^ C::fV(st_row[j])) << 4);
-  }
-  u32x4 kst[C::CPT], vst[C::CPT];
-  auto issue_loads = [&](int it) {
+  constexpr int NSTAGE = 3, STAGE_BYTES = 2 * C::TILE_BYTES;
+  constexpr int IPT = C::TILE_BYTES / 1024 / C::NW;   // 1 KB load instructions per wave, tile and tensor
+  constexpr int RPI = 1024 / C::RB;                   // rows per load instruction
+  static_assert(IPT >= 1 && NSTAGE == 3, "tile must split evenly over the waves");
+  const uint32_t smem_addr = (uint32_t)reinterpret_cast<uintptr_t>(smem);
+  const int ld_row0 = wave * RPI + lane / C::CPR;
+  const int ld_kcoff = ((lane % C::CPR) ^ C::fK(ld_row0)) * 16;
+  const int ld_vcoff = ((lane % C::CPR) ^ C::fV(ld_row0)) * 16;
+  auto issue_loads = [&](int it, int stage) __attribute__((always_inline)) {
     const bool is_ctx = it < n_ctx_run;
     const int key0 = is_ctx ? (b.c0 + it) * BN : (b.d0 + it - n_ctx_run) * BN;
-    const u16* kb = is_ctx ? kc_base : kd_base;
-    const u16* vb = is_ctx ? vc_base : vd_base;
-    const int64_t kts = is_ctx ? p.kc.ts : p.kd.ts, vts = is_ctx ? p.vc.ts : p.vd.ts;
-    const int nvalid = (is_ctx ? P : R) - key0;
+    const int kts = (int)(is_ctx ? p.kc.ts : p.kd.ts), vts = (int)(is_ctx ? p.vc.ts : p.vd.ts);
+    const u16* kb = uniform_ptr((is_ctx ? kc_base : kd_base) + (int64_t)key0 * kts);
+    const u16* vb = uniform_ptr((is_ctx ? vc_base : vd_base) + (int64_t)key0 * vts);
+    const int last = (is_ctx ? P : R) - key0 - 1;
+    const uint32_t dst = smem_addr + stage * STAGE_BYTES + wave * 1024;
 #pragma unroll
-    for (int j = 0; j < C::CPT; ++j) {
-      u32x4 zk = {0u, 0u, 0u, 0u}, zv = {0u, 0u, 0u, 0u};
-      if (st_row[j] < nvalid) {
-        zk = *reinterpret_cast<const u32x4*>(kb + (int64_t)(key0 + st_row[j]) * kts + st_col[j]);
-        zv = *reinterpret_cast<const u32x4*>(vb + (int64_t)(key0 + st_row[j]) * vts + st_col[j]);
-      }
-      kst[j] = zk;
-      vst[j] = zv;
+    for (int t = 0; t < IPT; ++t) {
+      const int r = min(ld_row0 + t * C::NW * RPI, last);
+      dma16(kb, (uint32_t)(r * kts * 2 + ld_kcoff), dst + t * C::NW * 1024);
+      dma16(vb, (uint32_t)(r * vts * 2 + ld_vcoff), dst + C::TILE_BYTES + t * C::NW * 1024);
     }
   };
-  auto store_stage = [&](int buf) {
-    unsigned char* kb = smem + buf * 2 * C::TILE_BYTES;
-    unsigned char* vb = kb + C::TILE_BYTES;
-#pragma unroll
-    for (int j = 0; j < C::CPT; ++j) {
-      *reinterpret_cast<u32x4*>(kb + st_koff[j]) = kst[j];
-      *reinterpret_cast<u32x4*>(vb + st_voff[j]) = vst[j];
-    }
+  // the tile consumed next must have landed; the 2 IPT loads of the tile after it may stay in flight
+  auto wait_loads = [&](bool newer_in_flight) __attribute__((always_inline)) {
+    wait_vm<2 * IPT>();
+    if (__builtin_expect(!newer_in_flight, 0)) wait_vm<0>();
   };
 
-  issue_loads(0);
-  store_stage(0);
-  if (b.n_tiles > 1) issue_loads(1);
+  issue_loads(0, 0);
+  if (b.n_tiles > 1) issue_loads(1, 1);
+  wait_loads(b.n_tiles > 1);
   __syncthreads();
 
+  int stage = 0;
   for (int it = 0; it < b.n_tiles; ++it) {
-    if (it + 1 < b.n_tiles) store_stage((it + 1) & 1);
-    if (it + 2 < b.n_tiles) issue_loads(it + 2);
+    // tile it+2 goes into the stage that tile it-1 left at the last barrier
+    if (it + 2 < b.n_tiles) issue_loads(it + 2, stage == 0 ? 2 : stage - 1);
 
-    const unsigned char* Kb = smem + (it & 1) * 2 * C::TILE_BYTES;
+    const unsigned char* Kb = smem + stage * STAGE_BYTES;
     const unsigned char* Vb = Kb + C::TILE_BYTES;
     const bool is_ctx = it < n_ctx_run;
     const int key0 = is_ctx ? (b.c0 + it) * BN : (b.d0 + it - n_ctx_run) * BN;
@@ -156,13 +156,14 @@ __global__ __launch_bounds__(DKV_FWD_NW * 64) void fwd2_kernel(const AttnParams 
         }
       }
       // instruction order: keep four K-operand reads in flight ahead of the MFMA that consumes them
-      __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+      constexpr int DEPTH = 4;
+      __builtin_amdgcn_sched_group_barrier(0x100, DEPTH, 0);
 #pragma unroll
-      for (int i = 0; i < C::KVSUB * C::KS - 4; ++i) {
+      for (int i = 0; i < C::KVSUB * C::KS - DEPTH; ++i) {
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
         __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
       }
-      __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, DEPTH, 0);
       if (tile_needs_mask<LOCAL, BN>(is_ctx, key0, row0, P, R, W)) {
 #pragma unroll
         for (int kv = 0; kv < C::KVSUB; ++kv)
@@ -216,7 +217,9 @@ __global__ __launch_bounds__(DKV_FWD_NW * 64) void fwd2_kernel(const AttnParams 
           }
         }
     }
+    wait_loads(it + 2 < b.n_tiles);
     __syncthreads();
+    stage = stage == 2 ? 0 : stage + 1;
   }
 
   const float l = xor32_sum(l_sum);
@@ -240,7 +243,7 @@ template <int D, bool LOCAL>
 static hipError_t launch_fwd2_t(AttnParams p, hipStream_t st) {
   using C = F2Cfg<D>;
   fill_packing(p, C::NW);
-  const size_t smem = 4 * C::TILE_BYTES;
+  const size_t smem = 3 * 2 * C::TILE_BYTES;
   auto kern = fwd2_kernel<D, LOCAL>;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
