@@ -61,9 +61,9 @@ extern "C" {
  * Call-1 + Call-2 sum (Eq. "dkc-total") is formed in fp32 and cast once by
  * dualkv_finalize_ctx_grads.  The caller zeroes the buffers before the first call. */
 #define DUALKV_FLAG_ACCUM_CTX_F32 1u
-/* Backward calls only: run a subset of the three backward stages (D = rowsum(dO*O) preprocess;
- * dK/dV; dQ).  Outputs of a skipped stage are left untouched.  The dK/dV and dQ stages read D from
- * the workspace, so DUALKV_FLAG_SKIP_PRE requires that an earlier call with the same inputs and the
+/* Backward calls only: run a subset of the three backward stages (preprocess: D = rowsum(dO*O) and
+ * LSE in base-2 units; dK/dV; dQ).  Outputs of a skipped stage are left untouched.  The dK/dV and dQ
+ * stages read the preprocess results from the workspace, so DUALKV_FLAG_SKIP_PRE requires that an earlier call with the same inputs and the
  * same workspace has run the preprocess.  For callers that need only some gradients, and for timing
  * the stages separately. */
 #define DUALKV_FLAG_SKIP_DQ   2u
