@@ -58,6 +58,9 @@ __device__ __forceinline__ float bf16_hi(uint32_t w) { return __builtin_bit_cast
 // every lane ends up with its own value in one register and its partner's in the other (no LDS round
 // trip).  Written as inline asm with both registers as read-write operands; the leading s_nop covers
 // the VALU-write -> permlane-read hazard the compiler cannot see.
+// NEVER feed an MFMA result straight into an inline-asm VALU instruction: the wait states between an MFMA and
+// a VALU read of its destination are inserted by the compiler, and it does not insert them for inline asm (the
+// instruction then reads the registers before the MFMA has written them; seen as run-to-run differences).
 __device__ __forceinline__ void swap32(float& a, float& b) {
   asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
 }

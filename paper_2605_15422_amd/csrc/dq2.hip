@@ -88,19 +88,24 @@ __global__ __launch_bounds__(512) void dq2_kernel(const AttnParams p) {
   const uint32_t smem_addr = (uint32_t)reinterpret_cast<uintptr_t>(smem);
   const int ld_row0 = wave * RPI + lane / CPR;
   const int ld_coff = ((lane % CPR) ^ swz<D>(ld_row0)) * 16;
+  // (token strides in bytes, read from the kernel arguments once: a scalar load inside the loop would make the
+  // wave wait for every LDS read in flight as well)
+  const int ktsb_c = (int)p.kc.ts * 2, ktsb_d = (int)p.kd.ts * 2, vtsb_c = (int)p.vc.ts * 2, vtsb_d = (int)p.vd.ts * 2;
   auto issue_loads = [&](int it, int stage) __attribute__((always_inline)) {
     const bool is_ctx = it < n_ctx_run;
     const int key0 = is_ctx ? (b.c0 + it) * BN : (b.d0 + it - n_ctx_run) * BN;
-    const int kts = (int)(is_ctx ? p.kc.ts : p.kd.ts), vts = (int)(is_ctx ? p.vc.ts : p.vd.ts);
-    const u16* kb = uniform_ptr((is_ctx ? kc_base : kd_base) + (int64_t)key0 * kts);
-    const u16* vb = uniform_ptr((is_ctx ? vc_base : vd_base) + (int64_t)key0 * vts);
+    const int ktsb = is_ctx ? ktsb_c : ktsb_d, vtsb = is_ctx ? vtsb_c : vtsb_d;
+    const u16* kb = uniform_ptr(reinterpret_cast<const u16*>(
+        reinterpret_cast<const unsigned char*>(is_ctx ? kc_base : kd_base) + (int64_t)key0 * ktsb));
+    const u16* vb = uniform_ptr(reinterpret_cast<const u16*>(
+        reinterpret_cast<const unsigned char*>(is_ctx ? vc_base : vd_base) + (int64_t)key0 * vtsb));
     const int last = (is_ctx ? P : R) - key0 - 1;
     const uint32_t dst = smem_addr + stage * STAGE_BYTES + wave * 1024;
 #pragma unroll
     for (int t = 0; t < IPT; ++t) {
-      const int row = min(ld_row0 + t * 8 * RPI, last);
-      dma16(kb, (uint32_t)(row * kts * 2 + ld_coff), dst + t * 8192);
-      dma16(vb, (uint32_t)(row * vts * 2 + ld_coff), dst + TILE_BYTES + t * 8192);
+      const unsigned row = (unsigned)min(ld_row0 + t * 8 * RPI, last);
+      dma16(kb, __umul24(row, (unsigned)ktsb) + ld_coff, dst + t * 8192);
+      dma16(vb, __umul24(row, (unsigned)vtsb) + ld_coff, dst + TILE_BYTES + t * 8192);
     }
   };
   // the tile consumed next must have landed; the 2 IPT loads of the tile after it may stay in flight
@@ -114,6 +119,12 @@ __global__ __launch_bounds__(512) void dq2_kernel(const AttnParams p) {
   wait_loads(b.n_tiles > 1);
   __syncthreads();
 
+  f32x16 negd;   // accumulator image of -D: this lane's query row in all sixteen registers
+#pragma unroll
+  for (int r = 0; r < 16; ++r) negd[r] = -dvec;
+  const bool never_plain = LOCAL || !wave_valid;
+  const int ctx_masked = (P % BN) ? b.n_ctx - 1 : -1;   // the partial last prompt tile
+  const int dec_masked = min(row0 + 1, R) / BN;         // response tiles from the diagonal (or the sequence end) on
   int stage = 0;
   for (int it = 0; it < b.n_tiles; ++it) {
     // tile it+2 goes into the stage that tile it-1 left at the last barrier
@@ -123,37 +134,50 @@ __global__ __launch_bounds__(512) void dq2_kernel(const AttnParams p) {
     const unsigned char* Kb = smem + stage * STAGE_BYTES;
     const unsigned char* Vb = Kb + TILE_BYTES;
     const bool is_ctx = it < n_ctx_run;
-    const int tile_key0 = is_ctx ? (b.c0 + it) * BN : (b.d0 + it - n_ctx_run) * BN;
+    const int kt = is_ctx ? b.c0 + it : b.d0 + it - n_ctx_run;
+    const int tile_key0 = kt * BN;
+    // most tiles are entirely visible to the 32 rows of this wave: no per-half tests for them
+    const bool plain = !never_plain && (is_ctx ? kt != ctx_masked : kt < dec_masked);
 
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
       const int key0 = tile_key0 + half * 32;
-      const bool active = wave_valid && tile_active<LOCAL, 32>(is_ctx, key0, row0, row0 + 31, P, W) &&
-                          key0 < (is_ctx ? P : R);
+      const bool active = plain || (wave_valid && tile_active<LOCAL, 32>(is_ctx, key0, row0, row0 + 31, P, W) &&
+                                    key0 < (is_ctx ? P : R));
       if (!active) continue;
-      f32x16 s, dpt;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        s[r] = 0.f;
-        dpt[r] = 0.f;
-      }
       const unsigned char* kh = Kb + half * 32 * RB;
       const unsigned char* vh = Vb + half * 32 * RB;
+      // S^T = K Q^T and dP^T - D = V dO^T - D (accumulator initialised to -D).  All 2 KS operand reads are
+      // requested first, in two groups; each group's MFMAs consume their operands in the reverse of the
+      // request order, so ONE wait per group covers them (an instruction of any kind costs the SIMD about
+      // as much issue time as a sixth of an MFMA: sixteen waits are not free).
+      bf16x8 ko[KS], vo[KS];
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
-        s = mfma32(*reinterpret_cast<const bf16x8*>(kh + roff[ks]), qf[ks], s);
-        dpt = mfma32(*reinterpret_cast<const bf16x8*>(vh + roff[ks]), dof[ks], dpt);
+        ko[ks] = *reinterpret_cast<const bf16x8*>(kh + roff[ks]);
+        vo[ks] = *reinterpret_cast<const bf16x8*>(vh + roff[ks]);
       }
-      // instruction order: keep four operand reads in flight ahead of the MFMA that consumes them (left alone,
-      // the compiler reads two operands, waits for them and issues two MFMAs: one LDS latency per pair)
-      __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      f32x16 s, dpt;
+      constexpr int G = KS / 2;
 #pragma unroll
-      for (int i = 0; i < 2 * KS - 4; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-      }
-      __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
-      const bool need = tile_needs_mask<LOCAL, 32>(is_ctx, key0, row0, P, R, W);
+      for (int g = 0; g < 2; ++g)
+#pragma unroll
+        for (int q = G - 1; q >= 0; --q) {
+          const int ks = g * G + q;
+          if (g == 0 && q == G - 1) {
+            f32x16 z;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) z[r] = 0.f;
+            dpt = mfma32(vo[ks], dof[ks], negd);
+            s = mfma32(ko[ks], qf[ks], z);
+          } else {
+            dpt = mfma32(vo[ks], dof[ks], dpt);
+            s = mfma32(ko[ks], qf[ks], s);
+          }
+        }
+      __builtin_amdgcn_sched_barrier(0);
+      const bool need = !plain && tile_needs_mask<LOCAL, 32>(is_ctx, key0, row0, P, R, W);
       float dsv[16];
       // two straight-line variants: a per-element test of a run-time flag costs three branches per element
       if (__builtin_expect(need, 0)) {
@@ -162,20 +186,20 @@ __global__ __launch_bounds__(512) void dq2_kernel(const AttnParams p) {
           float e = __builtin_amdgcn_exp2f(s[r] * c - lse2);
           const int key = key0 + crow(r, hi);
           if (!visible<LOCAL>(is_ctx, key, row, P, R, W)) e = 0.f;
-          dsv[r] = e * (dpt[r] - dvec);   // dS^T
+          dsv[r] = e * dpt[r];   // dS^T
         }
       } else {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) dsv[r] = __builtin_amdgcn_exp2f(s[r] * c - lse2) * (dpt[r] - dvec);
+        for (int r = 0; r < 16; ++r) dsv[r] = __builtin_amdgcn_exp2f(s[r] * c - lse2) * dpt[r];
       }
       // dQ^T += K^T dS^T
 #pragma unroll
       for (int t2 = 0; t2 < 2; ++t2) {
         const bf16x8 pb = pack8_bf16(dsv + t2 * 8);
-        const unsigned char* kt = kh + t2 * 16 * RB;
+        const unsigned char* kt2 = kh + t2 * 16 * RB;
 #pragma unroll
         for (int ds = 0; ds < DSUB; ++ds)
-          dqacc[ds] = mfma32(tr_pair(kt + toff0[ds], kt + toff1[ds]), pb, dqacc[ds]);
+          dqacc[ds] = mfma32(tr_pair(kt2 + toff0[ds], kt2 + toff1[ds]), pb, dqacc[ds]);
       }
     }
     wait_loads(it + 2 < b.n_tiles);
