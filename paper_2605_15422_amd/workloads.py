@@ -69,6 +69,12 @@ CONFIGS: Dict[str, Shape] = {
     "cfg4_30b":    Shape("cfg4_30b", 32, 16384, 1024, 8192, 32, 4, 128, 0, 1004),
     "cfg5a_global": Shape("cfg5a_global", 8, 57344, 8192, 8192, 8, 2, 512, 0, 1005),
     "cfg5b_swa":   Shape("cfg5b_swa", 8, 57344, 8192, 8192, 8, 2, 256, 1024, 1006),
+    # the (N, P) points of the paper's kernel benchmark (Tab. 1: Qwen3-8B dimensions, R = 2048 throughout);
+    # bench-only shapes that place this GPU's numbers beside the paper's
+    "tab1_n28_p4k":  Shape("tab1_n28_p4k", 28, 4096, 2048, 2048, 32, 8, 128, 0, 1101),
+    "tab1_n28_p16k": Shape("tab1_n28_p16k", 28, 16384, 2048, 2048, 32, 8, 128, 0, 1102),
+    "tab1_n16_p32k": Shape("tab1_n16_p32k", 16, 32768, 2048, 2048, 32, 8, 128, 0, 1103),
+    "tab1_n16_p64k": Shape("tab1_n16_p64k", 16, 65536, 2048, 2048, 32, 8, 128, 0, 1104),
     # shrunk replicas
     "cfg2_small":  Shape("cfg2_small", 4, 517, 131, 131, 8, 2, 128, 0, 2002),
     "cfg3_small":  Shape("cfg3_small", 6, 509, 17, 260, 8, 2, 128, 0, 2003),
