@@ -113,3 +113,33 @@ def test_layout_kernels():
         assert torch.equal(back, packed)
         want2 = np.concatenate([np.arange(P)] + [P + np.arange(l) for l in lens])
         assert np.array_equal(pos2.cpu().numpy(), want2)
+
+
+@pytest.mark.parametrize("name", ["cfg2_small", "cfg3_small", "cfg5b_small"])
+def test_run_to_run_determinism(name):
+    """Everything that is not summed with atomics is bitwise reproducible from run to run (different LDS and
+    register garbage, other kernels in between): catches reads of stale or not-yet-written data that stay
+    inside the parity tolerance.  dK_c / dV_c of these small shapes go through the split path (fp32 atomics
+    in an order that varies), so they are compared with a tolerance instead."""
+    import torch
+    from paper_2605_15422_amd import binding as B, runner
+    print("case determinism", name, flush=True)
+    wl = W.make_workload(W.CONFIGS[name])
+    dg = B.upload(wl)
+    ref = None
+    for rep in range(3):
+        b = runner.alloc(dg)
+        for t in (b.o_d, b.dq_d, b.dk_d, b.dv_d, b.o_c, b.dq_c):
+            t.fill_(float(rep))   # different leftovers in the outputs and, through the fills, in the caches
+        runner.layer_step(dg, b)
+        torch.cuda.synchronize()
+        if ref is None:
+            ref = b
+            continue
+        for n in ("o_c", "lse_c", "o_d", "lse_d", "dq_c", "dq_d", "dk_d", "dv_d"):
+            a, c = getattr(ref, n), getattr(b, n)
+            same = torch.equal(a.view(torch.int16), c.view(torch.int16)) if a.dtype == torch.bfloat16 else torch.equal(a, c)
+            assert same, (n, rep)
+        for n in ("dk_c1", "dv_c1", "dk_c2", "dv_c2"):
+            a, c = getattr(ref, n).float(), getattr(b, n).float()
+            assert float((a - c).abs().max()) <= 2e-2 + 2.0 ** -8 * float(a.abs().max()), (n, rep)
