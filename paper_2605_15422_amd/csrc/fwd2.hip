@@ -8,7 +8,8 @@
 //     16-byte K operand reads and the transposing V reads are bank-conflict free; V^T operands come
 //     from ds_read_b64_tr_b16 (LDS transpose read), so nothing is transposed on the way into LDS;
 //   * the tiles travel global -> LDS directly (global_load_lds) into two rings of four slots, K three
-//     tiles ahead and V two: no staging registers, no LDS stores, one barrier per tile;
+//     tiles ahead (requested by waves 0-3) and V two (waves 4-7): no staging registers, no LDS stores, one
+//     barrier per tile;
 //   * each wave runs a software pipeline over 32-key half tiles: while the VALU does the softmax of
 //     half g, the matrix pipe computes the scores of half g+1 and the P V product of half g-1.  Two
 //     waves per SIMD do not hide a wave's own MFMA -> softmax -> MFMA dependency chain on this chip
@@ -104,11 +105,15 @@ __global__ __launch_bounds__(DKV_FWD_NW * 64) void fwd2_kernel(const AttnParams 
   const int n_ctx_run = b.n_ctx - b.c0;
   constexpr int NSTAGE = 4;                           // ring slots per tensor: K ring, then V ring
   constexpr int V_RING = NSTAGE * C::TILE_BYTES;
-  constexpr int IPT = C::TILE_BYTES / 1024 / C::NW;   // 1 KB load instructions per wave, tile and tensor
+  // the K tiles are requested by waves 0-3, the V tiles by waves 4-7: one address computation per wave and tile
+  constexpr int LW = C::NW / 2;                       // waves per tensor
+  constexpr int IPT = C::TILE_BYTES / 1024 / LW;      // 1 KB load instructions per wave and tile
   constexpr int RPI = 1024 / C::RB;                   // rows per load instruction
   static_assert(IPT >= 1, "tile must split evenly over the waves");
   const uint32_t smem_addr = (uint32_t)reinterpret_cast<uintptr_t>(smem);
-  const int ld_row0 = wave * RPI + lane / C::CPR;
+  const int lwave = wave % LW;
+  const bool v_loader = wave >= LW;
+  const int ld_row0 = lwave * RPI + lane / C::CPR;
   const int ld_kcoff = ((lane % C::CPR) ^ C::fK(ld_row0)) * 16;
   const int ld_vcoff = ((lane % C::CPR) ^ C::fV(ld_row0)) * 16;
   // which = 0: K tile `it` into the K ring, 1: V tile `it` into the V ring (slot it % 4)
@@ -120,13 +125,13 @@ __global__ __launch_bounds__(DKV_FWD_NW * 64) void fwd2_kernel(const AttnParams 
     const u16* base = is_ctx ? (which ? vc_base : kc_base) : (which ? vd_base : kd_base);
     const unsigned char* tb = reinterpret_cast<const unsigned char*>(base) + (int64_t)(kt * BN) * tsb;
     const int last = (is_ctx ? P : R) - kt * BN - 1;
-    const uint32_t dst = smem_addr + which * V_RING + (it & (NSTAGE - 1)) * C::TILE_BYTES + wave * 1024;
+    const uint32_t dst = smem_addr + which * V_RING + (it & (NSTAGE - 1)) * C::TILE_BYTES + lwave * 1024;
     const int coff = which ? ld_vcoff : ld_kcoff;
 #pragma unroll
     for (int t = 0; t < IPT; ++t) {
-      const int r = min(ld_row0 + t * C::NW * RPI, last);
+      const int r = min(ld_row0 + t * LW * RPI, last);
       dma16(uniform_ptr(reinterpret_cast<const u16*>(tb)), (uint32_t)(__umul24((unsigned)r, (unsigned)tsb) + coff),
-            dst + t * C::NW * 1024);
+            dst + t * LW * 1024);
     }
   };
 
@@ -305,10 +310,14 @@ __global__ __launch_bounds__(DKV_FWD_NW * 64) void fwd2_kernel(const AttnParams 
   };
 
   // ---- prologue: K0 V0 K1 V1 K2 requested, everything landed and published, scores of the first half
-  issue_tile(0, 0);
-  issue_tile(0, 1);
-  if (b.n_tiles > 1) { issue_tile(1, 0); issue_tile(1, 1); }
-  if (b.n_tiles > 2) issue_tile(2, 0);
+  if (v_loader) {
+    issue_tile(0, 1);
+    if (b.n_tiles > 1) issue_tile(1, 1);
+  } else {
+    issue_tile(0, 0);
+    if (b.n_tiles > 1) issue_tile(1, 0);
+    if (b.n_tiles > 2) issue_tile(2, 0);
+  }
   wait_vm<0>();
   __syncthreads();
 
@@ -329,8 +338,14 @@ __global__ __launch_bounds__(DKV_FWD_NW * 64) void fwd2_kernel(const AttnParams 
     // K tile it+3 replaces K tile it-1, V tile it+2 replaces V tile it-2: both were last read before the
     // barrier that ended tile it-1
     const bool more = it + 3 < b.n_tiles;
-    if (more) issue_tile(it + 3, 0);
-    if (it + 2 < b.n_tiles) issue_tile(it + 2, 1);
+    bool issued;
+    if (v_loader) {
+      issued = it + 2 < b.n_tiles;
+      if (issued) issue_tile(it + 2, 1);
+    } else {
+      issued = more;
+      if (issued) issue_tile(it + 3, 0);
+    }
 
     const int slot = it & (NSTAGE - 1), slot_n = (it + 1) & (NSTAGE - 1), slot_p = (it > 0 ? it - 1 : 0) & (NSTAGE - 1);
     const unsigned char* Kt = smem + slot * C::TILE_BYTES;
@@ -346,7 +361,7 @@ __global__ __launch_bounds__(DKV_FWD_NW * 64) void fwd2_kernel(const AttnParams 
     step(masked, mxs, sA, sB, pB, pA, pre, Kt + 32 * C::RB, Vp, Kn, Vt, is_ctx, key0);
     step(masked, mxs, sB, sA, pA, pB, pre, Kn, Vt, Kn + 32 * C::RB, Vt + 32 * C::RB, is_ctx, key0 + 32);
     // tiles it+2 (K) and it+1 (V) must have landed; the loads requested at the top of this tile may stay in flight
-    if (more) wait_vm<2 * IPT>();
+    if (issued) wait_vm<IPT>();
     else wait_vm<0>();
     __syncthreads();
   }
