@@ -206,7 +206,9 @@ __global__ __launch_bounds__(512) void dkdv4_kernel(const AttnParams p) {
       const int nflags = __builtin_amdgcn_readfirstlane((int)hn.x);
       const int nrow0 = __builtin_amdgcn_readfirstlane((int)hn.y);
       const int nnvalid = __builtin_amdgcn_readfirstlane((int)hn.z);
-      if (__builtin_expect(nflags & HDR_ACTIVE, 1)) load_frags(IC<NU>{}, IC<0>{}, qfr);
+      // unconditional: a load that depends on the next header would make the compiler keep the old fragments in
+      // a second register set (sixteen moves per block); an inactive or invalid block's fragments are never used
+      load_frags(IC<NU>{}, IC<0>{}, qfr);
       __builtin_amdgcn_sched_barrier(0);
       unsigned char* xw = xw_lane + XB * XCH_BYTES;
       if (__builtin_expect(act, 1)) {
@@ -277,6 +279,12 @@ __global__ __launch_bounds__(512) void dkdv4_kernel(const AttnParams p) {
     const int ld_row0 = jb * RPI + lane / CPR;
     const int ld_coff = ((lane % CPR) ^ swz<D>(ld_row0)) * 16;
     const uint32_t ld_lds = smem_addr + jb * 1024;
+    // per-lane global offsets of this wave's load instructions for a block of 32 valid rows (a partial last
+    // block clamps its rows instead: rare, computed on the spot)
+    uint32_t voff_full[IPB];
+#pragma unroll
+    for (int t = 0; t < IPB; ++t)
+      voff_full[t] = LOCAL ? 0u : (uint32_t)((ld_row0 + (t % (IPB / 2)) * 4 * RPI) * (t < IPB / 2 ? q_ts : do_ts) * 2 + ld_coff);
     // row statistics: lanes 0-31 fetch LSE*log2e, lanes 32-63 fetch D; both arrays live in one workspace, D
     // first and LSE*log2e less than 4 GB behind it (checked by the launcher), so one scalar base plus an
     // unsigned 32-bit lane offset addresses both
@@ -372,11 +380,15 @@ __global__ __launch_bounds__(512) void dkdv4_kernel(const AttnParams p) {
         const int last = nvalid - 1;   // rows past the end of the sequence re-read its last row
         const u16* q_base = uniform_ptr(q_cur);
         const u16* do_base = uniform_ptr(do_cur);
+        const bool full = !LOCAL && nvalid == HB;   // (the windowed variant has no registers to spare for the table)
 #pragma unroll
         for (int t = 0; t < IPB; ++t) {
           const bool is_q = t < IPB / 2;
-          const int row = ld_row0 + (t % (IPB / 2)) * 4 * RPI;
-          const uint32_t voff = (uint32_t)(min(row, last) * (is_q ? q_ts : do_ts) * 2 + ld_coff);
+          uint32_t voff = voff_full[t];
+          if (__builtin_expect(!full, 0)) {
+            const int row = ld_row0 + (t % (IPB / 2)) * 4 * RPI;
+            voff = __umul24((unsigned)min(row, last), (unsigned)((is_q ? q_ts : do_ts) * 2)) + ld_coff;
+          }
           dma16(is_q ? q_base : do_base, voff,
                 ld_lds + (IS * STAGE_BYTES + (is_q ? 0 : HT_BYTES) + (t % (IPB / 2)) * 4096));
         }
