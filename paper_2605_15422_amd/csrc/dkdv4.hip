@@ -132,6 +132,9 @@ __global__ __launch_bounds__(512) void dkdv4_kernel(const AttnParams p) {
     const unsigned char* frag_lo[KS];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) frag_lo[ks] = smem + tile_off<D>(l32, 2 * ks + hi);
+    const unsigned char* frag_hi[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) frag_hi[ks] = frag_lo[ks] + HALF;
     const unsigned char* stat_lo = smem + STAT_OFF + hi * 16;   // this lane's rows 8*(r/4) + 4*hi + r%4
     const unsigned char* stat_hi = stat_lo + HALF;
     const unsigned char* hdr_lo = smem + HDR_OFF + kvs * 16;
@@ -150,13 +153,7 @@ __global__ __launch_bounds__(512) void dkdv4_kernel(const AttnParams p) {
       constexpr int U = decltype(Uc)::value;
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
-        const unsigned char* b = frag_lo[ks];
-        if (U >= NBUF / 2) {
-          // re-added per use (volatile: not hoisted out of the loop) instead of eight more live registers
-          uint32_t a = (uint32_t)reinterpret_cast<uintptr_t>(b);
-          asm volatile("v_add_u32 %0, %1, %0" : "+v"(a) : "s"(HALF));
-          b = smem + (a - (uint32_t)reinterpret_cast<uintptr_t>(smem));
-        }
+        const unsigned char* b = U >= NBUF / 2 ? frag_hi[ks] : frag_lo[ks];
         out[ks] = *reinterpret_cast<const bf16x8*>(b + (U % (NBUF / 2)) * STAGE_BYTES + decltype(which)::value * HT_BYTES);
       }
     };
