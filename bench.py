@@ -26,10 +26,10 @@ HBM_PEAK_GBS = 8000.0
 MEASURED_TRAFFIC_BYTES = {
     ("cfg2_qwen8b", "fwd"): 2 * 230643 * 1024 + 133131 * 1024,
     ("cfg2_qwen8b", "bwd_dq"): 2 * 297051 * 1024 + 131072 * 1024,
-    ("cfg2_qwen8b", "bwd_dkdv"): 2 * 785183 * 1024 + 98306 * 1024,
+    ("cfg2_qwen8b", "bwd_dkdv"): 2 * 785846 * 1024 + 99073 * 1024,
     ("cfg2_qwen8b", "ctx_fwd"): 2 * 72123 * 1024 + 66563 * 1024,
     ("cfg2_qwen8b", "ctx_bwd_dq"): 2 * 106473 * 1024 + 65536 * 1024,
-    ("cfg2_qwen8b", "ctx_bwd_dkdv"): 2 * 1605270 * 1024 + 32768 * 1024,
+    ("cfg2_qwen8b", "ctx_bwd_dkdv"): 2 * 1578960 * 1024 + 32768 * 1024,
 }
 
 
