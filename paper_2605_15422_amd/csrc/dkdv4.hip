@@ -377,17 +377,21 @@ __global__ __launch_bounds__(512) void dkdv4_kernel(const AttnParams p) {
         const int last = nvalid - 1;   // rows past the end of the sequence re-read its last row
         const u16* q_base = uniform_ptr(q_cur);
         const u16* do_base = uniform_ptr(do_cur);
-        const bool full = !LOCAL && nvalid == HB;   // (the windowed variant has no registers to spare for the table)
+        // (one branch for the whole block, not one per load)
+        if (__builtin_expect(!LOCAL && nvalid == HB, 1)) {
 #pragma unroll
-        for (int t = 0; t < IPB; ++t) {
-          const bool is_q = t < IPB / 2;
-          uint32_t voff = voff_full[t];
-          if (__builtin_expect(!full, 0)) {
+          for (int t = 0; t < IPB; ++t)
+            dma16(t < IPB / 2 ? q_base : do_base, voff_full[t],
+                  ld_lds + (IS * STAGE_BYTES + (t < IPB / 2 ? 0 : HT_BYTES) + (t % (IPB / 2)) * 4096));
+        } else {
+#pragma unroll
+          for (int t = 0; t < IPB; ++t) {
+            const bool is_q = t < IPB / 2;
             const int row = ld_row0 + (t % (IPB / 2)) * 4 * RPI;
-            voff = __umul24((unsigned)min(row, last), (unsigned)((is_q ? q_ts : do_ts) * 2)) + ld_coff;
+            const uint32_t voff = __umul24((unsigned)min(row, last), (unsigned)((is_q ? q_ts : do_ts) * 2)) + ld_coff;
+            dma16(is_q ? q_base : do_base, voff,
+                  ld_lds + (IS * STAGE_BYTES + (is_q ? 0 : HT_BYTES) + (t % (IPB / 2)) * 4096));
           }
-          dma16(is_q ? q_base : do_base, voff,
-                ld_lds + (IS * STAGE_BYTES + (is_q ? 0 : HT_BYTES) + (t % (IPB / 2)) * 4096));
         }
         if (wave == 5) {
           dma4(uniform_ptr(reinterpret_cast<const u16*>(stat_ptr + st_cur)), stat_lane_off + (uint32_t)min(l32, last) * 4u,
