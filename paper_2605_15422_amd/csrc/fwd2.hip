@@ -31,14 +31,11 @@ namespace dkv {
 template <int D>
 struct F2Cfg {
   static constexpr int NW = DKV_FWD_NW, NT = NW * 64, BN = 64;
-  static constexpr int KS = D / 16, DSUB = D / 32, KVSUB = BN / 32;
+  static constexpr int KS = D / 16, DSUB = D / 32;
   static constexpr int RB = 2 * D;                 // row bytes
   static constexpr int CPR = D / 8;                // 16-byte chunks per row
   static constexpr int RPL = CPR < 16 ? 16 / CPR : 1;   // rows per 256-byte bank line
   static constexpr int TILE_BYTES = BN * RB;
-  static constexpr int CHUNKS = BN * CPR;
-  static constexpr int CPT = CHUNKS / NT;          // chunks per thread (1 or 2)
-  static_assert(CHUNKS % NT == 0, "tile must split evenly over the threads");
   __device__ static __forceinline__ int fK(int row) { return (row / RPL) % CPR; }
   __device__ static __forceinline__ int fV(int row) { return 4 * ((row / RPL) % (CPR / 4)); }
 };
@@ -94,9 +91,9 @@ __global__ __launch_bounds__(DKV_FWD_NW * 64) void fwd2_kernel(const AttnParams 
     }
   }
 
-  // ---- global -> LDS tile loads: instruction j = wave + 8 t of a tile covers RPI key rows; lane l lands at
+  // ---- global -> LDS tile loads: instruction j = lwave + LW t of a tile covers RPI key rows; lane l lands at
   // LDS chunk position l % CPR of row l / CPR of the instruction and fetches the chunk the swizzle stores
-  // there (both swizzles have a period that divides 8 RPI rows, so one offset per tensor serves every t).
+  // there (both swizzles have a period that divides LW RPI rows, so one offset per tensor serves every t).
   // Keys past the end of the region re-read the last key: their scores are masked like any invisible key.
   const u16* kc_base = p.kc.ptr + (int64_t)b.hk * p.kc.hs;
   const u16* vc_base = p.vc.ptr + (int64_t)b.hk * p.vc.hs;
@@ -161,9 +158,9 @@ __global__ __launch_bounds__(DKV_FWD_NW * 64) void fwd2_kernel(const AttnParams 
   const u32x4 zero4 = {0u, 0u, 0u, 0u};
   // One step of the software pipeline: the softmax of half tile g (scores in `sc`) runs on the VALU while the
   // matrix pipe computes the scores of half g+1 (into `sn`) and accumulates the P V product of half g-1
-  // (`pprev`); the three are independent.  A SIMD issues roughly one instruction of ANY kind per 4.5-5 cycles
-  // over all its waves, so a 32-cycle MFMA leaves room for about six other instructions: the instruction
-  // count per MFMA, not a pipe, bounds this kernel, and the step is laid out to keep it low.  It consists of
+  // (`pprev`); the three are independent.  Measured on this chip, a SIMD issues one VALU-class instruction
+  // (MFMA included) per ~5 cycles over all its waves, so a 32-cycle MFMA hides about six of them if independent
+  // ones are next in the stream; the softmax needs 4.5 per MFMA at d = 128.  The step consists of
   // NSLOT slots of {one MFMA, the softmax of 16 / NSLOT scores} in groups of four.  All operand reads of a
   // group are requested at the start of the previous group, and a group's MFMAs consume their operands in the
   // reverse of the request order, so one wait per group covers them all; the softmax of a score is spread
