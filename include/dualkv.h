@@ -46,7 +46,7 @@ extern "C" {
 
 #define DUALKV_OK             0
 #define DUALKV_E_INVALID     (-1)  /* NULL pointer, negative size, H % H_k != 0, bad cu_seqlens ... */
-#define DUALKV_E_UNSUPPORTED (-2)  /* head_dim not in {64,128,256,512}; window with head_dim 512     */
+#define DUALKV_E_UNSUPPORTED (-2)  /* head_dim not in {64,96,128,192,256,512}; window with head_dim 512 */
 #define DUALKV_E_WORKSPACE   (-3)  /* workspace pointer NULL or smaller than dualkv_workspace_bytes  */
 #define DUALKV_E_ALIGN       (-4)  /* pointer not 16-byte aligned or stride not a multiple of 8      */
 #define DUALKV_E_HIP         (-5)  /* a HIP runtime call (launch) failed                             */
@@ -77,7 +77,7 @@ typedef struct dualkv_shape {
   int32_t max_resp;      /* max_i R_i                                                           */
   int32_t n_q_heads;     /* H                                                                   */
   int32_t n_kv_heads;    /* H_k, H % H_k == 0                                                   */
-  int32_t head_dim;      /* d in {64, 128, 256, 512}                                            */
+  int32_t head_dim;      /* d in {64, 96, 128, 192, 256, 512}                                   */
   int32_t window;        /* W > 0: sliding window of W keys incl. self; <= 0: none              */
   float   softmax_scale; /* <= 0 => 1/sqrt(d)                                                   */
   uint32_t flags;        /* DUALKV_FLAG_*                                                       */

@@ -25,7 +25,7 @@ int check_shape(const dualkv_shape* s, bool ctx_call) {
     if (s->total_resp > 0 && s->max_resp == 0) return DUALKV_E_INVALID;
   }
   const int d = s->head_dim;
-  if (d != 64 && d != 128 && d != 256 && d != 512) return DUALKV_E_UNSUPPORTED;
+  if (d != 64 && d != 96 && d != 128 && d != 192 && d != 256 && d != 512) return DUALKV_E_UNSUPPORTED;
   if (s->window > 0 && d == 512) return DUALKV_E_UNSUPPORTED;
   return DUALKV_OK;
 }
@@ -94,15 +94,15 @@ BwdWorkspace bwd_workspace(const dualkv_shape* s, bool ctx_call) {
 int hip_rc(hipError_t e) { return e == hipSuccess ? DUALKV_OK : DUALKV_E_HIP; }
 
 hipError_t run_fwd(const AttnParams& p, int d, hipStream_t st) {
-  if (d <= 128) return dkv::launch_fwd2(p, d, st);
+  if (d == 64 || d == 128) return dkv::launch_fwd2(p, d, st);
   return dkv::launch_fwd(p, d, st);
 }
 hipError_t run_dq(const AttnParams& p, int d, hipStream_t st) {
-  if (d <= 128) return dkv::launch_dq2(p, d, st);
+  if (d == 64 || d == 128) return dkv::launch_dq2(p, d, st);
   return dkv::launch_dq(p, d, st);
 }
 hipError_t run_dkdv(const AttnParams& p, int d, hipStream_t st) {
-  if (d <= 128) {
+  if (d == 64 || d == 128) {
     // the producer/consumer kernel needs the two statistics arrays within 4 GB of each other
     const bool near = reinterpret_cast<uintptr_t>(p.lse2) - reinterpret_cast<uintptr_t>(p.dvec) < (1ull << 32);
     return near ? dkv::launch_dkdv4(p, d, st) : dkv::launch_dkdv3(p, d, st);

@@ -14,7 +14,8 @@ template <int D>
 __global__ __launch_bounds__(256) void dot_do_o_kernel(TView dout, TView o, const float* __restrict__ lse,
                                                        float* __restrict__ dvec, float* __restrict__ lse2,
                                                        int total, int H) {
-  constexpr int LPR = D / 8;          // lanes per (row, head)
+  // lanes per (row, head): D / 8 of them carry data, rounded up to a power of two for the butterfly (d = 96, 192)
+  constexpr int LPR = D / 8 <= 8 ? 8 : D / 8 <= 16 ? 16 : D / 8 <= 32 ? 32 : 64;
   constexpr int RPB = 256 / LPR;      // (row, head) pairs per block
   const int tid = threadIdx.x;
   const int64_t pair = (int64_t)blockIdx.x * RPB + tid / LPR;
@@ -23,7 +24,7 @@ __global__ __launch_bounds__(256) void dot_do_o_kernel(TView dout, TView o, cons
   const bool ok = pair < (int64_t)total * H;
   const int64_t row = ok ? pair / H : 0;
   const int h = ok ? (int)(pair % H) : 0;
-  if (ok) {
+  if (ok && sub < D / 8) {
     const u32x4 a = *reinterpret_cast<const u32x4*>(dout.ptr + row * dout.ts + (int64_t)h * dout.hs + sub * 8);
     const u32x4 b = *reinterpret_cast<const u32x4*>(o.ptr + row * o.ts + (int64_t)h * o.hs + sub * 8);
     const uint32_t* aw = reinterpret_cast<const uint32_t*>(&a);
@@ -43,11 +44,13 @@ hipError_t launch_dot_do_o(const TView& dout, const TView& o, const float* lse, 
                            int H, int head_dim, hipStream_t st) {
   const int64_t pairs = (int64_t)total * H;
   if (pairs == 0) return hipSuccess;
-  const int lpr = head_dim / 8, rpb = 256 / lpr;
+  const int lanes = head_dim / 8, lpr = lanes <= 8 ? 8 : lanes <= 16 ? 16 : lanes <= 32 ? 32 : 64, rpb = 256 / lpr;
   const unsigned grid = (unsigned)((pairs + rpb - 1) / rpb);
   switch (head_dim) {
     case 64:  hipLaunchKernelGGL(dot_do_o_kernel<64>, dim3(grid), dim3(256), 0, st, dout, o, lse, dvec, lse2, total, H); break;
+    case 96:  hipLaunchKernelGGL(dot_do_o_kernel<96>, dim3(grid), dim3(256), 0, st, dout, o, lse, dvec, lse2, total, H); break;
     case 128: hipLaunchKernelGGL(dot_do_o_kernel<128>, dim3(grid), dim3(256), 0, st, dout, o, lse, dvec, lse2, total, H); break;
+    case 192: hipLaunchKernelGGL(dot_do_o_kernel<192>, dim3(grid), dim3(256), 0, st, dout, o, lse, dvec, lse2, total, H); break;
     case 256: hipLaunchKernelGGL(dot_do_o_kernel<256>, dim3(grid), dim3(256), 0, st, dout, o, lse, dvec, lse2, total, H); break;
     case 512: hipLaunchKernelGGL(dot_do_o_kernel<512>, dim3(grid), dim3(256), 0, st, dout, o, lse, dvec, lse2, total, H); break;
     default: return hipErrorInvalidValue;

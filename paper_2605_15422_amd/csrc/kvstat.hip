@@ -304,7 +304,9 @@ static hipError_t launch_dkdv_t(AttnParams p, hipStream_t st) {
 int dkdv_key_tile(int head_dim) {
   switch (head_dim) {
     case 64:  return KCfg<64, 1, 4, 64, 8>::BN;
+    case 96:  return KCfg<96, 1, 4, 64, 8>::BN;
     case 128: return KCfg<128, 1, 4, 64, 8>::BN;
+    case 192: return KCfg<192, 2, 4, 32, 8>::BN;
     case 256: return KCfg<256, 2, 4, 32, 8>::BN;
     case 512: return KCfg<512, 4, 4, 32, 0>::BN;
   }
@@ -315,7 +317,9 @@ hipError_t launch_dkdv(const AttnParams& p, int head_dim, hipStream_t st) {
   const bool local = p.window > 0;
   switch (head_dim) {
     case 64:  return local ? launch_dkdv_t<64, 1, 4, 64, 8, true>(p, st) : launch_dkdv_t<64, 1, 4, 64, 8, false>(p, st);
+    case 96:  return local ? launch_dkdv_t<96, 1, 4, 64, 8, true>(p, st) : launch_dkdv_t<96, 1, 4, 64, 8, false>(p, st);
     case 128: return local ? launch_dkdv_t<128, 1, 4, 64, 8, true>(p, st) : launch_dkdv_t<128, 1, 4, 64, 8, false>(p, st);
+    case 192: return local ? launch_dkdv_t<192, 2, 4, 32, 8, true>(p, st) : launch_dkdv_t<192, 2, 4, 32, 8, false>(p, st);
     case 256: return local ? launch_dkdv_t<256, 2, 4, 32, 8, true>(p, st) : launch_dkdv_t<256, 2, 4, 32, 8, false>(p, st);
     case 512: return launch_dkdv_t<512, 4, 4, 32, 0, false>(p, st);
   }

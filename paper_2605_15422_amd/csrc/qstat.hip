@@ -492,7 +492,9 @@ hipError_t launch_fwd(const AttnParams& p, int head_dim, hipStream_t st) {
   const bool local = p.window > 0;
   switch (head_dim) {
     case 64:  return local ? launch_fwd_t<64, 1, 2, 64, true>(p, st) : launch_fwd_t<64, 1, 2, 64, false>(p, st);
+    case 96:  return local ? launch_fwd_t<96, 1, 2, 64, true>(p, st) : launch_fwd_t<96, 1, 2, 64, false>(p, st);
     case 128: return local ? launch_fwd_t<128, 1, 2, 64, true>(p, st) : launch_fwd_t<128, 1, 2, 64, false>(p, st);
+    case 192: return local ? launch_fwd_t<192, 1, 1, 64, true>(p, st) : launch_fwd_t<192, 1, 1, 64, false>(p, st);
     case 256: return local ? launch_fwd_t<256, 1, 1, 64, true>(p, st) : launch_fwd_t<256, 1, 1, 64, false>(p, st);
     case 512: return launch_fwd_t<512, 2, 1, 32, false>(p, st);
   }
@@ -503,7 +505,9 @@ hipError_t launch_dq(const AttnParams& p, int head_dim, hipStream_t st) {
   const bool local = p.window > 0;
   switch (head_dim) {
     case 64:  return local ? launch_dq_t<64, 1, 2, 64, true>(p, st) : launch_dq_t<64, 1, 2, 64, false>(p, st);
+    case 96:  return local ? launch_dq_t<96, 1, 1, 64, true>(p, st) : launch_dq_t<96, 1, 1, 64, false>(p, st);
     case 128: return local ? launch_dq_t<128, 1, 1, 64, true>(p, st) : launch_dq_t<128, 1, 1, 64, false>(p, st);
+    case 192: return local ? launch_dq_t<192, 1, 1, 32, true>(p, st) : launch_dq_t<192, 1, 1, 32, false>(p, st);
     case 256: return local ? launch_dq_t<256, 1, 1, 32, true>(p, st) : launch_dq_t<256, 1, 1, 32, false>(p, st);
     case 512: return launch_dq_t<512, 2, 1, 32, false>(p, st);
   }

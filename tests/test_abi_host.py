@@ -41,7 +41,7 @@ def test_argument_validation_before_launch():
 
     assert ws()[0] == B.OK and ws()[1] >= 6 * 4 * 4
     assert ws(n_q_heads=5)[0] == B.E_INVALID            # H % H_k != 0
-    assert ws(head_dim=96)[0] == B.E_UNSUPPORTED
+    assert ws(head_dim=80)[0] == B.E_UNSUPPORTED
     assert ws(head_dim=512, window=16)[0] == B.E_UNSUPPORTED
     assert ws(n_seqs=0)[0] == B.E_INVALID
     assert ws(ctx_len=-1)[0] == B.E_INVALID

@@ -38,6 +38,10 @@ EDGE = [
     ("win_huge", 2, 100, [60, 70], 4, 2, 256, 4096),
     ("d512_tail", 2, 65, [33, 70], 2, 1, 512, 0),
     ("exact_tiles", 2, 256, [128, 64], 4, 2, 128, 0),
+    ("d96", 2, 150, [70, 41], 4, 2, 96, 0),
+    ("d96_win", 2, 130, [90, 33], 2, 2, 96, 40),
+    ("d192", 3, 200, [33, 130, 64], 6, 2, 192, 0),
+    ("d192_win", 2, 140, [64, 90], 4, 2, 192, 50),
 ]
 
 
