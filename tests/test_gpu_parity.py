@@ -147,3 +147,47 @@ def test_run_to_run_determinism(name):
         for n in ("dk_c1", "dv_c1", "dk_c2", "dv_c2"):
             a, c = getattr(ref, n).float(), getattr(b, n).float()
             assert float((a - c).abs().max()) <= 2e-2 + 2.0 ** -8 * float(a.abs().max()), (n, rep)
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_growing_scores_exercise_the_lazy_rescale(d):
+    """Scores whose magnitude grows along the key axis (queries x4, key norms ramping up 0.5 -> 2): the running
+    reference maximum of the forward kernel moves many times, so the path that accumulates the pending P V product
+    before rescaling runs often; everything must still match the oracle within the stated tolerances."""
+    print("case growing_scores", d, flush=True)
+    shape = W.Shape("growing_scores", 3, 333, 0, 0, 4, 2, d, 0, seed=9090 + d)
+    wl = W.make_workload(shape, resp_lens=np.asarray([190, 77, 260]))
+
+    def scaled(bits, factor):
+        x = W.bf16_bits_to_f32(bits) * factor
+        return W.f32_to_bf16_bits(x.astype(np.float32))
+
+    wl.q_c = scaled(wl.q_c, 4.0)
+    wl.q_d = scaled(wl.q_d, 4.0)
+    ramp_c = (0.5 + 1.5 * np.arange(wl.k_c.shape[0]) / max(1, wl.k_c.shape[0] - 1)).astype(np.float32)
+    wl.k_c = scaled(wl.k_c, ramp_c[:, None, None])
+    ramp_d = np.empty(wl.k_d.shape[0], dtype=np.float32)
+    for i in range(len(wl.resp_lens)):
+        lo, hi = int(wl.cu_seqlens[i]), int(wl.cu_seqlens[i + 1])
+        ramp_d[lo:hi] = 0.5 + 1.5 * np.arange(hi - lo) / max(1, hi - lo - 1)
+    wl.k_d = scaled(wl.k_d, ramp_d[:, None, None])
+    x = PU.oracle_inputs(wl)
+    ref = PU.orc.dualkv_reference(x["q_c"], x["k_c"], x["v_c"], x["q_d"], x["k_d"], x["v_d"], wl.cu_seqlens, wl.scale,
+                                  x["do_c"], x["do_d"], wl.shape.window)
+    dg, b = PU.run_hip_layer(wl)
+    rep = []
+    PU.compare("O_c", PU.to_f64(b.o_c), ref["o_c"], rep)
+    PU.compare_lse("LSE_c", PU.to_f64(b.lse_c), ref["lse_c"], rep)
+    PU.compare("O_d", PU.to_f64(b.o_d), ref["o_d"], rep)
+    PU.compare_lse("LSE_d", PU.to_f64(b.lse_d), ref["lse_d"], rep)
+    # the inputs are four times the usual size here, and so are the bf16 rounding errors of the dS operands: the
+    # gradients are held to the relative bound only
+    for name, got, want in (("dQ_d", b.dq_d, ref["call2"]["dq_d"]), ("dK_d", b.dk_d, ref["call2"]["dk_d"]),
+                            ("dV_d", b.dv_d, ref["call2"]["dv_d"]), ("dQ_c", b.dq_c, ref["call1"]["dq_c"]),
+                            ("dK_c(2)", b.dk_c2, ref["call2"]["dk_c"]), ("dV_c(2)", b.dv_c2, ref["call2"]["dv_c"])):
+        g = PU.to_f64(got)
+        assert np.isfinite(g).all(), name
+        rel = float(np.linalg.norm(g - want) / np.linalg.norm(want))
+        rep.append("%-8s relL2=%.3e" % (name, rel))
+        assert rel <= PU.REL_L2, (name, rel)
+    print("\n  " + "\n  ".join(rep), flush=True)
