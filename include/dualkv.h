@@ -148,6 +148,18 @@ int dualkv_replicate(int32_t n_seqs, int32_t ctx_len, int32_t total_resp, const 
                      int64_t row_bytes, const void* packed, void* standard, int32_t* position_ids,
                      void* stream);
 
+/* Next-token map of the single-prompt packing (Sec. 2.3, "shared prompt logits"; the rolled labels and other
+ * per-token side tensors of the packed sequence are gathered with it).  Device outputs, either may be NULL:
+ *   next_index        (P + total_resp) int32: packed row t predicts the token at packed row next_index[t];
+ *                     -1 where it predicts nothing through this map (last prompt row, last row of a response).
+ *                     Prompt rows and response rows shift by one inside their own segment.
+ *   first_token_index (N) int32: the first token of response i sits at packed row P + cu[i] and is predicted
+ *                     by the logits of the LAST PROMPT ROW P - 1, shared by all N responses; -1 for an empty
+ *                     response or when there is no prompt.
+ * Errors: DUALKV_E_INVALID for n_seqs < 1, negative sizes, a NULL cu_seqlens_dev or more than 2^31 - 1 rows. */
+int dualkv_label_map(int32_t n_seqs, int32_t ctx_len, int32_t total_resp, const int32_t* cu_seqlens_dev,
+                     int32_t* next_index, int32_t* first_token_index, void* stream);
+
 const char* dualkv_strerror(int code);
 int dualkv_version(void);
 

@@ -358,3 +358,20 @@ def visible_pairs_call2(P, resp_lens, window=0):
 def visible_pairs_replicated(P, resp_lens, window=0):
     """Visible pairs per head of the N-copy baseline (Eq. 2): sum_i causal pairs of length P+R_i."""
     return sum(visible_pairs_call1(P + int(R), window) for R in resp_lens)
+
+
+# --------------------------------------------------------------------------
+# next-token map of the single-prompt packing (Sec. 2.3, "shared prompt logits")
+# --------------------------------------------------------------------------
+def next_token_pairs_replicated(P, cu):
+    """Set of (predicting packed row, predicted packed row) pairs, from the definition: in every replica
+    [prompt ; response i] of the standard packing, row s predicts row s + 1; rows are then renamed to the
+    single-prompt packing (prompt row j -> j for every replica, response i row r -> P + cu[i] + r)."""
+    pairs = set()
+    for i in range(len(cu) - 1):
+        R = int(cu[i + 1] - cu[i])
+        packed = list(range(P)) + [P + int(cu[i]) + r for r in range(R)]
+        for s in range(P + R - 1):
+            pairs.add((packed[s], packed[s + 1]))
+    return pairs
+

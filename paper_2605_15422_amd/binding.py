@@ -31,8 +31,8 @@ FLAG_SKIP_DKDV = 4
 FLAG_SKIP_PRE = 8
 
 EXPORTS = ["dualkv_workspace_bytes", "dualkv_ctx_fwd", "dualkv_ctx_bwd", "dualkv_fwd", "dualkv_bwd",
-           "dualkv_finalize_ctx_grads", "dualkv_repack", "dualkv_replicate", "dualkv_strerror",
-           "dualkv_version"]
+           "dualkv_finalize_ctx_grads", "dualkv_repack", "dualkv_replicate", "dualkv_label_map",
+           "dualkv_strerror", "dualkv_version"]
 
 
 class Shape(C.Structure):
@@ -67,6 +67,7 @@ lib.dualkv_finalize_ctx_grads.argtypes = [_PS, C.c_void_p, C.c_void_p, TOut, TOu
 for _f in (lib.dualkv_repack, lib.dualkv_replicate):
     _f.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
                    C.c_void_p, C.c_void_p]
+lib.dualkv_label_map.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
 for _n in EXPORTS:
     if _n not in ("dualkv_strerror",):
         getattr(lib, _n).restype = C.c_int
@@ -191,6 +192,11 @@ def dualkv_repack(n_seqs, ctx_len, total_resp, cu_seqlens_dev, row_bytes, standa
 def dualkv_replicate(n_seqs, ctx_len, total_resp, cu_seqlens_dev, row_bytes, packed, standard, position_ids=None):
     _check(lib.dualkv_replicate(n_seqs, ctx_len, total_resp, _ptr(cu_seqlens_dev), row_bytes, _ptr(packed),
                                 _ptr(standard), _ptr(position_ids), _stream()), "dualkv_replicate")
+
+
+def dualkv_label_map(n_seqs, ctx_len, total_resp, cu_seqlens_dev, next_index=None, first_token_index=None):
+    _check(lib.dualkv_label_map(n_seqs, ctx_len, total_resp, _ptr(cu_seqlens_dev), _ptr(next_index),
+                                _ptr(first_token_index), _stream()), "dualkv_label_map")
 
 
 # --------------------------------------------------------------------------

@@ -390,4 +390,12 @@ int dualkv_replicate(int32_t n_seqs, int32_t ctx_len, int32_t total_resp, const 
                           position_ids, stream);
 }
 
+int dualkv_label_map(int32_t n_seqs, int32_t ctx_len, int32_t total_resp, const int32_t* cu_seqlens_dev,
+                     int32_t* next_index, int32_t* first_token_index, void* stream) {
+  if (n_seqs < 1 || ctx_len < 0 || total_resp < 0 || cu_seqlens_dev == nullptr) return DUALKV_E_INVALID;
+  if ((int64_t)ctx_len + total_resp > 0x7fffffff) return DUALKV_E_INVALID;
+  return hip_rc(dkv::launch_label_map(n_seqs, ctx_len, total_resp, cu_seqlens_dev, next_index, first_token_index,
+                                      static_cast<hipStream_t>(stream)));
+}
+
 }  // extern "C"

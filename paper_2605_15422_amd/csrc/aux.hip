@@ -174,4 +174,46 @@ hipError_t launch_rows_copy(bool to_packed, int n_seqs, int ctx_len, int total_r
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------------------
+// Next-token map of the single-prompt packing (Sec. 2.3 "shared prompt logits"): packed row t predicts the
+// token at packed row next_index[t] (-1: nothing).  Prompt rows and response rows shift by one inside their own
+// segment; the row of the last prompt token predicts the FIRST token of every response, which cannot be
+// expressed per row: first_token_index[i] (row P + cu[i], or -1 for an empty response or P = 0) lists them, all
+// read from row P - 1.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void label_map_kernel(int n_seqs, int P, int total_resp,
+                                                        const int32_t* __restrict__ cu, int32_t* __restrict__ next_index,
+                                                        int32_t* __restrict__ first_token_index) {
+  const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t T = (int64_t)P + total_resp;
+  if (next_index != nullptr && t < T) {
+    int nxt;
+    if (t < P) {
+      nxt = t + 1 < P ? (int)(t + 1) : -1;
+    } else {
+      const int x = (int)(t - P);
+      int lo = 0, hi = n_seqs;   // find i with cu[i] <= x < cu[i+1]
+      while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (cu[mid] <= x) lo = mid; else hi = mid;
+      }
+      nxt = x + 1 < cu[lo + 1] ? (int)(t + 1) : -1;
+    }
+    next_index[t] = nxt;
+  }
+  if (first_token_index != nullptr && t < n_seqs) {
+    const int i = (int)t;
+    first_token_index[i] = (P > 0 && cu[i + 1] > cu[i]) ? P + cu[i] : -1;
+  }
+}
+
+hipError_t launch_label_map(int n_seqs, int ctx_len, int total_resp, const int32_t* cu, int32_t* next_index,
+                            int32_t* first_token_index, hipStream_t st) {
+  const int64_t n = max((int64_t)ctx_len + total_resp, (int64_t)n_seqs);
+  if (n == 0) return hipSuccess;
+  hipLaunchKernelGGL(label_map_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, n_seqs, ctx_len,
+                     total_resp, cu, next_index, first_token_index);
+  return hipGetLastError();
+}
+
 }  // namespace dkv

@@ -24,5 +24,7 @@ hipError_t launch_convert_ctx(const float* acc, const TViewOut& out, int P, int 
                               hipStream_t st);
 hipError_t launch_rows_copy(bool to_packed, int n_seqs, int ctx_len, int total_resp, const int32_t* cu,
                             int64_t row_bytes, const void* src, void* dst, int32_t* pos_ids, hipStream_t st);
+hipError_t launch_label_map(int n_seqs, int ctx_len, int total_resp, const int32_t* cu, int32_t* next_index,
+                            int32_t* first_token_index, hipStream_t st);
 
 }  // namespace dkv

@@ -119,6 +119,31 @@ def test_layout_kernels():
         assert np.array_equal(pos2.cpu().numpy(), want2)
 
 
+@pytest.mark.parametrize("P,lens", [(37, [5, 0, 19, 8]), (1, [1]), (0, [4, 2]), (300, [0, 0, 700, 1, 64]), (5, [0])])
+def test_label_map(P, lens):
+    """Next-token map of the packed layout (Sec. 2.3) against the oracle's definition by explicit replication."""
+    import torch
+    from oracle import attention_oracle as orc
+    from paper_2605_15422_amd import binding as B
+    print("case label_map", P, lens, flush=True)
+    N = len(lens)
+    cu = np.zeros(N + 1, dtype=np.int32)
+    cu[1:] = np.cumsum(lens)
+    T = int(cu[-1])
+    cu_dev = torch.from_numpy(cu).cuda()
+    nxt = torch.full((max(P + T, 1),), -7, dtype=torch.int32, device="cuda")
+    first = torch.full((N,), -7, dtype=torch.int32, device="cuda")
+    B.dualkv_label_map(N, P, T, cu_dev, nxt, first)
+    nxt, first = nxt.cpu().numpy()[:P + T], first.cpu().numpy()
+    got = {(t, int(n)) for t, n in enumerate(nxt) if n >= 0}
+    got |= {(P - 1, int(f)) for f in first if f >= 0}
+    assert got == orc.next_token_pairs_replicated(P, cu)
+    assert all(n >= -1 for n in nxt) and all(f >= -1 for f in first)
+    # either output may be left out
+    B.dualkv_label_map(N, P, T, cu_dev, None, torch.from_numpy(first).cuda())
+    B.dualkv_label_map(N, P, T, cu_dev, torch.from_numpy(nxt).cuda() if P + T else None, None)
+
+
 @pytest.mark.parametrize("name", ["cfg2_small", "cfg3_small", "cfg5b_small"])
 def test_run_to_run_determinism(name):
     """Everything that is not summed with atomics is bitwise reproducible from run to run (different LDS and

@@ -374,3 +374,33 @@ def test_pair_counts_by_enumeration():
         assert orc.visible_pairs_replicated(P, lens, W) == cr
         # N-copy = N prompt passes + the response rows
         assert cr == len(lens) * c1 + c2
+
+
+def test_next_token_pairs_hand_example_and_coverage():
+    """The next-token map of the packed layout (Sec. 2.3): a hand-written example, and the property that
+    pins it in general: every packed row except row 0 is predicted exactly once, and only the last prompt row
+    predicts more than one row (the first token of every non-empty response)."""
+    # P = 3, responses of 2, 0 and 1 tokens: packed rows 0 1 2 | 3 4 | | 5
+    cu = np.array([0, 2, 2, 3])
+    want = {(0, 1), (1, 2), (2, 3), (3, 4), (2, 5)}
+    assert orc.next_token_pairs_replicated(3, cu) == want
+    rng = np.random.default_rng(11)
+    for _ in range(20):
+        P = int(rng.integers(1, 9))
+        lens = rng.integers(0, 6, size=int(rng.integers(1, 6)))
+        cu = np.concatenate([[0], np.cumsum(lens)])
+        pairs = orc.next_token_pairs_replicated(P, cu)
+        T = P + int(cu[-1])
+        targets = sorted(b for _, b in pairs)
+        assert targets == list(range(1, T))                      # each row but the first is predicted once
+        fan = {}
+        for a, b in pairs:
+            fan.setdefault(a, []).append(b)
+        for a, bs in fan.items():
+            if a == P - 1:
+                assert sorted(bs) == [P + int(cu[i]) for i in range(len(lens)) if lens[i] > 0]
+            else:
+                assert bs == [a + 1]
+    # no prompt: plain per-sequence shift, nothing predicts a first token
+    assert orc.next_token_pairs_replicated(0, np.array([0, 2, 3])) == {(0, 1)}
+
