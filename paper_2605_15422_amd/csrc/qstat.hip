@@ -18,9 +18,9 @@
 
 namespace dkv {
 
-template <int D, int DSPLIT, int QSUB, int BN>
+template <int D, int DSPLIT, int QSUB, int BN, int NWAVES>
 struct QCfg {
-  static constexpr int NW = 4;
+  static constexpr int NW = NWAVES;
   static constexpr int NT = NW * WAVE;
   static constexpr int RG = NW / DSPLIT;         // row groups (waves that own distinct rows)
   static constexpr int NST = RG * QSUB;          // 32-row subtiles per workgroup
@@ -36,9 +36,9 @@ struct QCfg {
 // ---------------------------------------------------------------------------------------------
 // forward
 // ---------------------------------------------------------------------------------------------
-template <int D, int DSPLIT, int QSUB, int BN, bool LOCAL>
-__global__ __launch_bounds__(256) void fwd_kernel(const AttnParams p) {
-  using C = QCfg<D, DSPLIT, QSUB, BN>;
+template <int D, int DSPLIT, int QSUB, int BN, int NW, bool LOCAL>
+__global__ __launch_bounds__(NW * 64) void fwd_kernel(const AttnParams p) {
+  using C = QCfg<D, DSPLIT, QSUB, BN, NW>;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   u16* Ks = reinterpret_cast<u16*>(smem_raw);                 // [BN][KPITCH]
   u16* VTs = Ks + BN * C::KPITCH;                             // [D][TPITCH]
@@ -251,14 +251,14 @@ __global__ __launch_bounds__(256) void fwd_kernel(const AttnParams p) {
 // (Alg. 1, inner loop), evaluated per query block over all its visible key tiles so that dQ is
 // accumulated in registers and written once -- no fp32 dQ scratch, no atomics, no convert pass.
 // ---------------------------------------------------------------------------------------------
-template <int D, int DSPLIT, int QSUB, int BN, bool LOCAL>
-__global__ __launch_bounds__(256) void dq_kernel(const AttnParams p) {
-  using C = QCfg<D, DSPLIT, QSUB, BN>;
+template <int D, int DSPLIT, int QSUB, int BN, int NW, bool LOCAL>
+__global__ __launch_bounds__(NW * 64) void dq_kernel(const AttnParams p) {
+  using C = QCfg<D, DSPLIT, QSUB, BN, NW>;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   u16* Ks = reinterpret_cast<u16*>(smem_raw);                 // [BN][KPITCH]
   u16* Vs = Ks + BN * C::KPITCH;                              // [BN][KPITCH]
   u16* KTs = Vs + BN * C::KPITCH;                             // [D][TPITCH]
-  float* xch = reinterpret_cast<float*>(KTs + D * C::TPITCH); // [2][NW][KVSUB*16][64] (DSPLIT > 1)
+  float* xch = reinterpret_cast<float*>(KTs + D * C::TPITCH); // [NW][KVSUB*16][64] (DSPLIT > 1)
 
   QBlock b;
   if (!decode_qblock<BN>(p, b)) return;
@@ -364,33 +364,30 @@ __global__ __launch_bounds__(256) void dq_kernel(const AttnParams p) {
       }
     }
     if (DSPLIT > 1) {
+      // sum the partial S, then the partial dP, of the waves that split the head dim (one buffer, used twice)
       constexpr int PER = C::KVSUB * 16;
-      float* x0 = xch;
-      float* x1 = xch + C::NW * PER * 64;
-      if (active) {
 #pragma unroll
-        for (int kv = 0; kv < C::KVSUB; ++kv)
+      for (int which = 0; which < 2; ++which) {
+        if (which) __syncthreads();
+        if (active) {
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            x0[(wave * PER + kv * 16 + r) * 64 + lane] = s[0][kv][r];
-            x1[(wave * PER + kv * 16 + r) * 64 + lane] = dpt[0][kv][r];
-          }
-      }
-      __syncthreads();
-      if (active) {
+          for (int kv = 0; kv < C::KVSUB; ++kv)
 #pragma unroll
-        for (int kv = 0; kv < C::KVSUB; ++kv)
+            for (int r = 0; r < 16; ++r)
+              xch[(wave * PER + kv * 16 + r) * 64 + lane] = which ? dpt[0][kv][r] : s[0][kv][r];
+        }
+        __syncthreads();
+        if (active) {
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            float a0 = 0.f, a1 = 0.f;
+          for (int kv = 0; kv < C::KVSUB; ++kv)
 #pragma unroll
-            for (int w2 = 0; w2 < DSPLIT; ++w2) {
-              a0 += x0[((rg * DSPLIT + w2) * PER + kv * 16 + r) * 64 + lane];
-              a1 += x1[((rg * DSPLIT + w2) * PER + kv * 16 + r) * 64 + lane];
+            for (int r = 0; r < 16; ++r) {
+              float acc = 0.f;
+#pragma unroll
+              for (int w2 = 0; w2 < DSPLIT; ++w2) acc += xch[((rg * DSPLIT + w2) * PER + kv * 16 + r) * 64 + lane];
+              if (which) dpt[0][kv][r] = acc; else s[0][kv][r] = acc;
             }
-            s[0][kv][r] = a0;
-            dpt[0][kv][r] = a1;
-          }
+        }
       }
     }
 
@@ -456,47 +453,51 @@ __global__ __launch_bounds__(256) void dq_kernel(const AttnParams p) {
 // ---------------------------------------------------------------------------------------------
 // host launchers
 // ---------------------------------------------------------------------------------------------
-template <int D, int DSPLIT, int QSUB, int BN, bool LOCAL>
+template <int D, int DSPLIT, int QSUB, int BN, int NW, bool LOCAL>
 static hipError_t launch_fwd_t(AttnParams p, hipStream_t st) {
-  using C = QCfg<D, DSPLIT, QSUB, BN>;
+  using C = QCfg<D, DSPLIT, QSUB, BN, NW>;
   fill_packing(p, C::NST);
   size_t smem = (size_t)(BN * C::KPITCH + D * C::TPITCH) * 2;
   if (DSPLIT > 1) smem += (size_t)C::NW * C::KVSUB * 16 * 64 * 4;
-  auto kern = fwd_kernel<D, DSPLIT, QSUB, BN, LOCAL>;
+  auto kern = fwd_kernel<D, DSPLIT, QSUB, BN, NW, LOCAL>;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
   if (e != hipSuccess) return e;
   const int64_t nblk = (int64_t)p.n_seqs * p.MB * p.HC * p.Hk;
   if (nblk == 0) return hipSuccess;
-  hipLaunchKernelGGL(kern, dim3((unsigned)nblk), dim3(256), smem, st, p);
+  hipLaunchKernelGGL(kern, dim3((unsigned)nblk), dim3(NW * 64), smem, st, p);
   return hipGetLastError();
 }
 
-template <int D, int DSPLIT, int QSUB, int BN, bool LOCAL>
+template <int D, int DSPLIT, int QSUB, int BN, int NW, bool LOCAL>
 static hipError_t launch_dq_t(AttnParams p, hipStream_t st) {
-  using C = QCfg<D, DSPLIT, QSUB, BN>;
+  using C = QCfg<D, DSPLIT, QSUB, BN, NW>;
   fill_packing(p, C::NST);
   size_t smem = (size_t)(2 * BN * C::KPITCH + D * C::TPITCH) * 2;
-  if (DSPLIT > 1) smem += (size_t)2 * C::NW * C::KVSUB * 16 * 64 * 4;
-  auto kern = dq_kernel<D, DSPLIT, QSUB, BN, LOCAL>;
+  if (DSPLIT > 1) smem += (size_t)C::NW * C::KVSUB * 16 * 64 * 4;
+  auto kern = dq_kernel<D, DSPLIT, QSUB, BN, NW, LOCAL>;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
   if (e != hipSuccess) return e;
   const int64_t nblk = (int64_t)p.n_seqs * p.MB * p.HC * p.Hk;
   if (nblk == 0) return hipSuccess;
-  hipLaunchKernelGGL(kern, dim3((unsigned)nblk), dim3(256), smem, st, p);
+  hipLaunchKernelGGL(kern, dim3((unsigned)nblk), dim3(NW * 64), smem, st, p);
   return hipGetLastError();
 }
 
+// Per head dim: <D, DSPLIT, QSUB, BN, NW>.  Head dims 256 (forward) and 512 split the head dim over the waves of
+// a row group and run eight waves, two per SIMD: the per-wave state then fits 256 registers without spills, which
+// more than pays for the exchange of partial scores through LDS (measured: forward 256 1.55x, dQ 512 1.9x faster
+// than four waves with twice the registers each; dQ 256 is faster unsplit).
 hipError_t launch_fwd(const AttnParams& p, int head_dim, hipStream_t st) {
   const bool local = p.window > 0;
   switch (head_dim) {
-    case 64:  return local ? launch_fwd_t<64, 1, 2, 64, true>(p, st) : launch_fwd_t<64, 1, 2, 64, false>(p, st);
-    case 96:  return local ? launch_fwd_t<96, 1, 2, 64, true>(p, st) : launch_fwd_t<96, 1, 2, 64, false>(p, st);
-    case 128: return local ? launch_fwd_t<128, 1, 2, 64, true>(p, st) : launch_fwd_t<128, 1, 2, 64, false>(p, st);
-    case 192: return local ? launch_fwd_t<192, 1, 1, 64, true>(p, st) : launch_fwd_t<192, 1, 1, 64, false>(p, st);
-    case 256: return local ? launch_fwd_t<256, 1, 1, 64, true>(p, st) : launch_fwd_t<256, 1, 1, 64, false>(p, st);
-    case 512: return launch_fwd_t<512, 2, 1, 32, false>(p, st);
+    case 64:  return local ? launch_fwd_t<64, 1, 2, 64, 4, true>(p, st) : launch_fwd_t<64, 1, 2, 64, 4, false>(p, st);
+    case 96:  return local ? launch_fwd_t<96, 1, 2, 64, 4, true>(p, st) : launch_fwd_t<96, 1, 2, 64, 4, false>(p, st);
+    case 128: return local ? launch_fwd_t<128, 1, 2, 64, 4, true>(p, st) : launch_fwd_t<128, 1, 2, 64, 4, false>(p, st);
+    case 192: return local ? launch_fwd_t<192, 1, 1, 64, 4, true>(p, st) : launch_fwd_t<192, 1, 1, 64, 4, false>(p, st);
+    case 256: return local ? launch_fwd_t<256, 2, 1, 64, 8, true>(p, st) : launch_fwd_t<256, 2, 1, 64, 8, false>(p, st);
+    case 512: return launch_fwd_t<512, 4, 1, 32, 8, false>(p, st);
   }
   return hipErrorInvalidValue;
 }
@@ -504,12 +505,12 @@ hipError_t launch_fwd(const AttnParams& p, int head_dim, hipStream_t st) {
 hipError_t launch_dq(const AttnParams& p, int head_dim, hipStream_t st) {
   const bool local = p.window > 0;
   switch (head_dim) {
-    case 64:  return local ? launch_dq_t<64, 1, 2, 64, true>(p, st) : launch_dq_t<64, 1, 2, 64, false>(p, st);
-    case 96:  return local ? launch_dq_t<96, 1, 1, 64, true>(p, st) : launch_dq_t<96, 1, 1, 64, false>(p, st);
-    case 128: return local ? launch_dq_t<128, 1, 1, 64, true>(p, st) : launch_dq_t<128, 1, 1, 64, false>(p, st);
-    case 192: return local ? launch_dq_t<192, 1, 1, 32, true>(p, st) : launch_dq_t<192, 1, 1, 32, false>(p, st);
-    case 256: return local ? launch_dq_t<256, 1, 1, 32, true>(p, st) : launch_dq_t<256, 1, 1, 32, false>(p, st);
-    case 512: return launch_dq_t<512, 2, 1, 32, false>(p, st);
+    case 64:  return local ? launch_dq_t<64, 1, 2, 64, 4, true>(p, st) : launch_dq_t<64, 1, 2, 64, 4, false>(p, st);
+    case 96:  return local ? launch_dq_t<96, 1, 1, 64, 4, true>(p, st) : launch_dq_t<96, 1, 1, 64, 4, false>(p, st);
+    case 128: return local ? launch_dq_t<128, 1, 1, 64, 4, true>(p, st) : launch_dq_t<128, 1, 1, 64, 4, false>(p, st);
+    case 192: return local ? launch_dq_t<192, 1, 1, 32, 4, true>(p, st) : launch_dq_t<192, 1, 1, 32, 4, false>(p, st);
+    case 256: return local ? launch_dq_t<256, 1, 1, 32, 4, true>(p, st) : launch_dq_t<256, 1, 1, 32, 4, false>(p, st);
+    case 512: return launch_dq_t<512, 4, 1, 32, 8, false>(p, st);
   }
   return hipErrorInvalidValue;
 }
