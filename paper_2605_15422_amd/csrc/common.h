@@ -89,10 +89,14 @@ __device__ __forceinline__ int kperm4(int k4) {  // k4 = k / 4
 // A tile is ROWS x D bf16 taken from `ROWS` consecutive token rows of one head.  Thread t owns
 // "units" of 4 rows x 8 columns (four 16-byte loads), so it can write both the row-major image
 // (4 x 16 B) and the transposed, kperm-ordered image (8 x 8 B) without any cross-lane traffic.
+// Consecutive threads take consecutive row quads of one 8-column chunk: their 8-byte writes into the
+// transposed image are then contiguous within an image row (with consecutive chunks per thread they land
+// eight image rows apart, on two banks: the transposed stores then cost 40 % of the head-dim-512 dK/dV kernel).
 // ---------------------------------------------------------------------------------------------
 template <int ROWS, int D, int NT>
 struct TileRegs {
   static constexpr int CH = D / 8;                       // 16-byte chunks per row
+  static constexpr int RQ = ROWS / 4;                    // row quads; consecutive threads take consecutive quads
   static constexpr int NUNITS = (ROWS / 4) * CH;
   static constexpr int UPT = (NUNITS + NT - 1) / NT;     // units per thread
   u32x4 v[UPT][4];
@@ -102,7 +106,7 @@ struct TileRegs {
 #pragma unroll
     for (int u = 0; u < UPT; ++u) {
       const int unit = tid + u * NT;
-      const int ch = unit % CH, rq = unit / CH;
+      const int rq = unit % RQ, ch = unit / RQ;
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         const int row = rq * 4 + j;
@@ -120,7 +124,7 @@ struct TileRegs {
     for (int u = 0; u < UPT; ++u) {
       const int unit = tid + u * NT;
       if (NUNITS % NT != 0 && unit >= NUNITS) continue;
-      const int ch = unit % CH, rq = unit / CH;
+      const int rq = unit % RQ, ch = unit / RQ;
 #pragma unroll
       for (int j = 0; j < 4; ++j)
         *reinterpret_cast<u32x4*>(lds + (rq * 4 + j) * pitch + ch * 8) = v[u][j];
@@ -133,7 +137,7 @@ struct TileRegs {
     for (int u = 0; u < UPT; ++u) {
       const int unit = tid + u * NT;
       if (NUNITS % NT != 0 && unit >= NUNITS) continue;
-      const int ch = unit % CH, rq = unit / CH;
+      const int rq = unit % RQ, ch = unit / RQ;
       const int pos = kperm4(rq) * 4;
       const uint32_t* w0 = reinterpret_cast<const uint32_t*>(&v[u][0]);
       const uint32_t* w1 = reinterpret_cast<const uint32_t*>(&v[u][1]);
