@@ -36,7 +36,11 @@ struct KCfg {
   // the exchange buffer of a head-dim split ([NW][16][64] floats) lies over the row-major images, which are
   // dead by then (one row subtile per step)
   static_assert(DSPLIT == 1 || (QSUB == 1 && NW * 16 * 64 * 4 <= 2 * BM * QPITCH * 2), "exchange buffer overlay");
-  static constexpr size_t smem_bytes() { return (size_t)(2 * BM * QPITCH + 2 * D * TPITCH) * 2 + 2 * BM * 4; }
+  static constexpr size_t smem_bytes() {
+    size_t s = (size_t)(2 * BM * QPITCH + 2 * D * TPITCH) * 2 + 2 * BM * 4;
+    if (DSPLIT > 1) s += (size_t)KVS * 2 * 64 * 8 * 4;   // bf16 operand images of P and dS per key group
+    return s;
+  }
 };
 
 template <int D, int DSPLIT, int NW, int BM, int TPAD, bool LOCAL>
@@ -51,6 +55,7 @@ __global__ __launch_bounds__(NW * 64) void dkdv_kernel(const AttnParams p) {
   float* lseL = reinterpret_cast<float*>(dOTs + D * C::TPITCH);  // [BM] LSE * log2(e)
   float* DL = lseL + BM;                                // [BM]
   float* xch = reinterpret_cast<float*>(smem_raw);      // [NW][16][64] (DSPLIT > 1), over Qs / dOs
+  uint32_t* pbuf = reinterpret_cast<uint32_t*>(DL + BM); // [KVS][P | dS][64 lanes][8 words] (DSPLIT > 1)
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, hi = lane >> 5;
@@ -190,11 +195,19 @@ __global__ __launch_bounds__(NW * 64) void dkdv_kernel(const AttnParams p) {
           dpv = mfma32(*reinterpret_cast<const bf16x8*>(da + ks * 16), vf[ks], dpv);
         }
       }
+      bf16x8 pa[2], dsa[2];   // P^T and dS^T of the subtile as MFMA operands (k-steps 0, 1 over the 32 rows)
       if (DSPLIT > 1) {
-        // sum the partial S, then the partial dP, of the waves that split the head dim
+        // The waves of a key group hold partial S and dP tiles (their part of the head dim).  Each of them sums
+        // RPW of the 16 accumulator registers over the group (S, then dP, through one buffer), evaluates P and dS
+        // for those, and publishes them as bf16 words of the operand image [lane][8 words]; every wave then
+        // reads the whole image: 2 x 16 bytes per operand instead of DSPLIT x 16 partial values, and each
+        // exponential is evaluated once per key group.
+        constexpr int RPW = 16 / DSPLIT;
+        float ssum[RPW], dsum[RPW];
         __syncthreads();   // every wave has read its row-major operands: the buffer may overwrite them
 #pragma unroll
         for (int which = 0; which < 2; ++which) {
+          if (which) __syncthreads();
           if (active) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) xch[(wave * 16 + r) * 64 + lane] = which ? dpv[r] : s[r];
@@ -202,17 +215,46 @@ __global__ __launch_bounds__(NW * 64) void dkdv_kernel(const AttnParams p) {
           __syncthreads();
           if (active) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
+            for (int j = 0; j < RPW; ++j) {
               float acc = 0.f;
 #pragma unroll
-              for (int w2 = 0; w2 < DSPLIT; ++w2) acc += xch[((kvs * DSPLIT + w2) * 16 + r) * 64 + lane];
-              if (which) dpv[r] = acc; else s[r] = acc;
+              for (int w2 = 0; w2 < DSPLIT; ++w2) acc += xch[((kvs * DSPLIT + w2) * 16 + dp * RPW + j) * 64 + lane];
+              if (which) dsum[j] = acc; else ssum[j] = acc;
             }
           }
-          __syncthreads();
         }
-      }
-      if (active) {
+        uint32_t* img = pbuf + kvs * (2 * 64 * 8);
+        if (active) {
+          float pv[RPW], dsv[RPW];
+#pragma unroll
+          for (int j = 0; j < RPW; ++j) {
+            const int rl = crow(dp * RPW + j, hi);
+            float e = exp2f(ssum[j] * c - lseL[qs * 32 + rl]);
+            if (need_mask) {
+              const int row = srow0 + rl;
+              bool ok;
+              if (is_ctx) ok = !LOCAL || (my_key > P + row - W);
+              else ok = (my_key <= row) && (!LOCAL || (my_key > row - W));
+              if (!ok) e = 0.f;
+            }
+            pv[j] = e;
+            dsv[j] = e * (dsum[j] - DL[qs * 32 + rl]);
+          }
+#pragma unroll
+          for (int w = 0; w < RPW / 2; ++w) {
+            img[lane * 8 + dp * (RPW / 2) + w] = pack2_bf16(pv[2 * w], pv[2 * w + 1]);
+            img[64 * 8 + lane * 8 + dp * (RPW / 2) + w] = pack2_bf16(dsv[2 * w], dsv[2 * w + 1]);
+          }
+        }
+        __syncthreads();
+        if (active) {
+#pragma unroll
+          for (int t2 = 0; t2 < 2; ++t2) {
+            pa[t2] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(img + lane * 8 + t2 * 4));
+            dsa[t2] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(img + 64 * 8 + lane * 8 + t2 * 4));
+          }
+        }
+      } else if (active) {
         float lr[16], dr[16];
 #pragma unroll
         for (int r4 = 0; r4 < 4; ++r4) {
@@ -240,15 +282,19 @@ __global__ __launch_bounds__(NW * 64) void dkdv_kernel(const AttnParams p) {
         }
 #pragma unroll
         for (int t2 = 0; t2 < 2; ++t2) {
-          const bf16x8 pa = pack8_bf16(pv + t2 * 8);
-          const bf16x8 dsa = pack8_bf16(dsv + t2 * 8);
+          pa[t2] = pack8_bf16(pv + t2 * 8);
+          dsa[t2] = pack8_bf16(dsv + t2 * 8);
+        }
+      }
+      if (active) {
+#pragma unroll
+        for (int t2 = 0; t2 < 2; ++t2)
 #pragma unroll
           for (int ds = 0; ds < C::DSUB; ++ds) {
             const int off = (dp * C::DC + ds * 32 + l32) * C::TPITCH + qs * 32 + t2 * 16 + hi * 8;
-            dv[ds] = mfma32(pa, *reinterpret_cast<const bf16x8*>(dOTs + off), dv[ds]);
-            dk[ds] = mfma32(dsa, *reinterpret_cast<const bf16x8*>(QTs + off), dk[ds]);
+            dv[ds] = mfma32(pa[t2], *reinterpret_cast<const bf16x8*>(dOTs + off), dv[ds]);
+            dk[ds] = mfma32(dsa[t2], *reinterpret_cast<const bf16x8*>(QTs + off), dk[ds]);
           }
-        }
       }
     }
     __syncthreads();

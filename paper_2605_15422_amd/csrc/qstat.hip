@@ -259,6 +259,7 @@ __global__ __launch_bounds__(NW * 64) void dq_kernel(const AttnParams p) {
   u16* Vs = Ks + BN * C::KPITCH;                              // [BN][KPITCH]
   u16* KTs = Vs + BN * C::KPITCH;                             // [D][TPITCH]
   float* xch = reinterpret_cast<float*>(KTs + D * C::TPITCH); // [NW][KVSUB*16][64] (DSPLIT > 1)
+  uint32_t* pbuf = reinterpret_cast<uint32_t*>(xch + C::NW * C::KVSUB * 16 * 64);   // [RG][KVSUB][64 lanes][8 words]
 
   QBlock b;
   if (!decode_qblock<BN>(p, b)) return;
@@ -363,9 +364,14 @@ __global__ __launch_bounds__(NW * 64) void dq_kernel(const AttnParams p) {
         }
       }
     }
+    uint32_t* img = pbuf + rg * (C::KVSUB * 64 * 8);   // dS^T operand image of the row group (DSPLIT > 1)
     if (DSPLIT > 1) {
-      // sum the partial S, then the partial dP, of the waves that split the head dim (one buffer, used twice)
-      constexpr int PER = C::KVSUB * 16;
+      // The waves of a row group hold partial S and dP tiles (their part of the head dim).  Each of them sums RPW
+      // of the 16 accumulator registers of every subtile over the group (S, then dP, through one buffer),
+      // evaluates dS for those and publishes it as bf16 words of the operand image [lane][8 words]; every wave
+      // then reads the whole image, and each exponential is evaluated once per row group.
+      constexpr int PER = C::KVSUB * 16, RPW = 16 / DSPLIT;
+      float ssum[C::KVSUB][RPW], dsum[C::KVSUB][RPW];
 #pragma unroll
       for (int which = 0; which < 2; ++which) {
         if (which) __syncthreads();
@@ -381,23 +387,43 @@ __global__ __launch_bounds__(NW * 64) void dq_kernel(const AttnParams p) {
 #pragma unroll
           for (int kv = 0; kv < C::KVSUB; ++kv)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
+            for (int j = 0; j < RPW; ++j) {
               float acc = 0.f;
 #pragma unroll
-              for (int w2 = 0; w2 < DSPLIT; ++w2) acc += xch[((rg * DSPLIT + w2) * PER + kv * 16 + r) * 64 + lane];
-              if (which) dpt[0][kv][r] = acc; else s[0][kv][r] = acc;
+              for (int w2 = 0; w2 < DSPLIT; ++w2)
+                acc += xch[((rg * DSPLIT + w2) * PER + kv * 16 + dp * RPW + j) * 64 + lane];
+              if (which) dsum[kv][j] = acc; else ssum[kv][j] = acc;
             }
         }
       }
-    }
-
-    if (active) {
+      if (active) {
+        const int row = row0[0] + l32;
+        const bool need = tile_needs_mask<LOCAL, BN>(is_ctx, key0, row0[0], P, R, W);
+#pragma unroll
+        for (int kv = 0; kv < C::KVSUB; ++kv) {
+          float dsv[RPW];
+#pragma unroll
+          for (int j = 0; j < RPW; ++j) {
+            float e = exp2f(ssum[kv][j] * c - lse2[0]);
+            if (need) {
+              const int key = key0 + kv * 32 + crow(dp * RPW + j, hi);
+              if (!visible<LOCAL>(is_ctx, key, row, P, R, W)) e = 0.f;
+            }
+            dsv[j] = e * (dsum[kv][j] - dvec[0]);
+          }
+#pragma unroll
+          for (int w = 0; w < RPW / 2; ++w)
+            img[(kv * 64 + lane) * 8 + dp * (RPW / 2) + w] = pack2_bf16(dsv[2 * w], dsv[2 * w + 1]);
+        }
+      }
+      __syncthreads();
+    } else if (active) {
 #pragma unroll
       for (int qs = 0; qs < QSUB; ++qs) {
         const int row = row0[qs] + l32;
         const bool need = tile_needs_mask<LOCAL, BN>(is_ctx, key0, row0[qs], P, R, W);
 #pragma unroll
-        for (int kv = 0; kv < C::KVSUB; ++kv)
+        for (int kv = 0; kv < C::KVSUB; ++kv) {
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
             float e = exp2f(s[qs][kv][r] * c - lse2[qs]);
@@ -407,19 +433,27 @@ __global__ __launch_bounds__(NW * 64) void dq_kernel(const AttnParams p) {
             }
             s[qs][kv][r] = e * (dpt[qs][kv][r] - dvec[qs]);   // dS^T
           }
+        }
       }
+    }
+
+    if (active) {
       // dQ^T += K^T dS^T
 #pragma unroll
       for (int kv = 0; kv < C::KVSUB; ++kv)
 #pragma unroll
         for (int t2 = 0; t2 < 2; ++t2) {
           bf16x8 pb[QSUB];
+          if (DSPLIT > 1) {
+            pb[0] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(img + (kv * 64 + lane) * 8 + t2 * 4));
+          } else {
 #pragma unroll
-          for (int qs = 0; qs < QSUB; ++qs) {
-            float tmp[8];
+            for (int qs = 0; qs < QSUB; ++qs) {
+              float tmp[8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) tmp[e] = s[qs][kv][t2 * 8 + e];
-            pb[qs] = pack8_bf16(tmp);
+              for (int e = 0; e < 8; ++e) tmp[e] = s[qs][kv][t2 * 8 + e];
+              pb[qs] = pack8_bf16(tmp);
+            }
           }
 #pragma unroll
           for (int ds = 0; ds < C::DSUB; ++ds) {
@@ -474,7 +508,7 @@ static hipError_t launch_dq_t(AttnParams p, hipStream_t st) {
   using C = QCfg<D, DSPLIT, QSUB, BN, NW>;
   fill_packing(p, C::NST);
   size_t smem = (size_t)(2 * BN * C::KPITCH + D * C::TPITCH) * 2;
-  if (DSPLIT > 1) smem += (size_t)C::NW * C::KVSUB * 16 * 64 * 4;
+  if (DSPLIT > 1) smem += (size_t)C::NW * C::KVSUB * 16 * 64 * 4 + (size_t)C::RG * C::KVSUB * 64 * 8 * 4;
   auto kern = dq_kernel<D, DSPLIT, QSUB, BN, NW, LOCAL>;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
