@@ -46,7 +46,8 @@ extern "C" {
 
 #define DUALKV_OK             0
 #define DUALKV_E_INVALID     (-1)  /* NULL pointer, negative size, H % H_k != 0, bad cu_seqlens ... */
-#define DUALKV_E_UNSUPPORTED (-2)  /* head_dim not in {64,96,128,192,256,512}; window with head_dim 512 */
+#define DUALKV_E_UNSUPPORTED (-2)  /* head_dim not in {64,96,128,192,256,512}; window with head_dim 512;
+                                      tok_stride > DUALKV_MAX_TOK_STRIDE                                   */
 #define DUALKV_E_WORKSPACE   (-3)  /* workspace pointer NULL or smaller than dualkv_workspace_bytes  */
 #define DUALKV_E_ALIGN       (-4)  /* pointer not 16-byte aligned or stride not a multiple of 8      */
 #define DUALKV_E_HIP         (-5)  /* a HIP runtime call (launch) failed                             */
@@ -83,6 +84,11 @@ typedef struct dualkv_shape {
   uint32_t flags;        /* DUALKV_FLAG_*                                                       */
 } dualkv_shape;
 
+/* A tensor view: device pointer (16-byte aligned) to element (token 0, head 0, 0) of a bf16 tensor whose head_dim
+ * axis is contiguous; strides in ELEMENTS, multiples of 8 and >= head_dim.  tok_stride may not exceed
+ * DUALKV_MAX_TOK_STRIDE (the kernels form the byte offset of a row inside a tile in 32 bits); larger strides are
+ * rejected with DUALKV_E_UNSUPPORTED. */
+#define DUALKV_MAX_TOK_STRIDE (1 << 22)
 typedef struct dualkv_tin  { const void* ptr; int64_t tok_stride; int64_t head_stride; } dualkv_tin;
 typedef struct dualkv_tout { void*       ptr; int64_t tok_stride; int64_t head_stride; } dualkv_tout;
 

@@ -36,6 +36,7 @@ int check_view(const void* ptr, int64_t ts, int64_t hs, int64_t rows, int d) {
   if (reinterpret_cast<uintptr_t>(ptr) % 16 != 0) return DUALKV_E_ALIGN;
   if (ts % 8 != 0 || hs % 8 != 0) return DUALKV_E_ALIGN;
   if (ts < d || hs < d) return DUALKV_E_INVALID;
+  if (ts > DUALKV_MAX_TOK_STRIDE) return DUALKV_E_UNSUPPORTED;   // the kernels form row offsets in 32 bits
   return DUALKV_OK;
 }
 int check_in(const dualkv_tin& t, int64_t rows, int d) { return check_view(t.ptr, t.tok_stride, t.head_stride, rows, d); }

@@ -101,18 +101,25 @@ struct TileRegs {
   static constexpr int UPT = (NUNITS + NT - 1) / NT;     // units per thread
   u32x4 v[UPT][4];
 
-  // base: pointer to (row 0, column 0) of the tile; rows >= nvalid are zero-filled
+  // base: pointer to (row 0, column 0) of the tile (the same for every thread); rows >= nvalid are zero-filled.
+  // Addresses are the uniform base plus a 32-bit byte offset per thread (token strides are bounded by the API),
+  // one register per load instead of a 64-bit pointer pair: with pointer pairs the d = 512 dQ kernel spilled them
+  // and waited for each load before it could issue the next.
   __device__ __forceinline__ void load(const u16* base, int64_t tok_stride, int nvalid, int tid) {
+    const unsigned char* b8 = reinterpret_cast<const unsigned char*>(base);
+    const uint32_t sb = (uint32_t)tok_stride * 2u;
 #pragma unroll
     for (int u = 0; u < UPT; ++u) {
       const int unit = tid + u * NT;
       const int rq = unit % RQ, ch = unit / RQ;
+      uint32_t off0 = (uint32_t)(rq * 4) * sb + (uint32_t)(ch * 16);
+      asm volatile("" : "+v"(off0));   // keeps the zero extension next to the load (base + 32-bit offset form)
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         const int row = rq * 4 + j;
         u32x4 z = {0u, 0u, 0u, 0u};
         if ((NUNITS % NT == 0 || unit < NUNITS) && row < nvalid)
-          z = *reinterpret_cast<const u32x4*>(base + (int64_t)row * tok_stride + ch * 8);
+          z = *reinterpret_cast<const u32x4*>(b8 + (off0 + (uint32_t)j * sb));
         v[u][j] = z;
       }
     }

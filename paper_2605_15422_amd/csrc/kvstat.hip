@@ -137,7 +137,8 @@ __global__ __launch_bounds__(NW * 64) void dkdv_kernel(const AttnParams p) {
     doreg.load(p.dout.ptr + s.grow * p.dout.ts + (int64_t)s.head * p.dout.hs, p.dout.ts, s.nvalid, tid);
     if (tid < BM) {
       const bool ok = tid < s.nvalid;
-      lse_pf = ok ? p.lse[(int64_t)s.head * p.total + s.grow + tid] * LOG2E : LSE_MASKED;
+      // (scaled by log2(e) when it is stored to LDS: arithmetic on the value here would wait for every load in flight)
+      lse_pf = ok ? p.lse[(int64_t)s.head * p.total + s.grow + tid] : LSE_MASKED;
       d_pf = ok ? p.dvec[(int64_t)s.head * p.total + s.grow + tid] : 0.f;
     }
   };
@@ -153,7 +154,7 @@ __global__ __launch_bounds__(NW * 64) void dkdv_kernel(const AttnParams p) {
     doreg.store_rowmajor(dOs, C::QPITCH, tid);
     doreg.store_transposed(dOTs, C::TPITCH, tid);
     if (tid < BM) {
-      lseL[tid] = lse_pf;
+      lseL[tid] = lse_pf * LOG2E;
       DL[tid] = d_pf;
     }
     __syncthreads();

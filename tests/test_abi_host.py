@@ -70,6 +70,9 @@ def test_argument_validation_before_launch():
     fake = B.TIn(0x1000, 252, 64)                        # stride not a multiple of 8
     rc = B.lib.dualkv_ctx_fwd(C.byref(s), fake, fake, fake, B.TOut(0x1000, 256, 64), None, None, 0, None)
     assert rc == B.E_ALIGN
+    fake = B.TIn(0x1000, (1 << 22) + 8, 64)              # token stride beyond the 32-bit row offsets of the kernels
+    rc = B.lib.dualkv_ctx_fwd(C.byref(s), fake, fake, fake, B.TOut(0x1000, 256, 64), None, None, 0, None)
+    assert rc == B.E_UNSUPPORTED
     good = B.TIn(0x1000, 256, 64)
     goodo = B.TOut(0x1000, 256, 64)
     rc = B.lib.dualkv_ctx_bwd(C.byref(s), good, good, C.c_void_p(0x1000), good, good, good, goodo, goodo, goodo,
