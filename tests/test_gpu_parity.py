@@ -216,3 +216,26 @@ def test_growing_scores_exercise_the_lazy_rescale(d):
         rep.append("%-8s relL2=%.3e" % (name, rel))
         assert rel <= PU.REL_L2, (name, rel)
     print("\n  " + "\n  ".join(rep), flush=True)
+
+
+def test_random_small_shapes():
+    """Sixty seeded random shapes: every head dim, GQA ratios 1-8, windows from 1 key up, prompts of 0-300 and
+    responses of 0-190 tokens (lengths around the 32/64-key tile edges), with and without fp32 joint accumulation."""
+    from paper_2605_15422_amd import binding as B
+    rng = np.random.default_rng(11)
+    for i in range(60):
+        d = int(rng.choice([64, 96, 128, 192, 256, 512]))
+        hk = int(rng.choice([1, 2, 3]))
+        g = int(rng.choice([1, 2, 3, 4, 8])) if d <= 128 else int(rng.choice([1, 2, 4]))
+        n = int(rng.integers(1, 6))
+        P = int(rng.choice([0, 1, 31, 32, 33, 64, 100, 129, 255, 300]))
+        lens = [int(x) for x in rng.choice([0, 1, 2, 31, 32, 33, 63, 64, 65, 100, 129, 190], size=n)]
+        if sum(lens) == 0:
+            lens[0] = 17
+        win = 0
+        if d != 512 and rng.random() < 0.4:
+            win = int(rng.choice([1, 2, 16, 33, 64, 100, 257]))
+        flags = B.FLAG_ACCUM_CTX_F32 if rng.random() < 0.25 else 0
+        print("case random", i, dict(d=d, H=hk * g, Hk=hk, N=n, P=P, lens=lens, win=win, flags=flags), flush=True)
+        shape = W.Shape("rnd%d" % i, n, P, 0, 0, hk * g, hk, d, win, seed=9000 + i)
+        PU.full_parity(W.make_workload(shape, resp_lens=np.asarray(lens)), flags=flags, verbose=False)
