@@ -242,6 +242,7 @@ def main():
         "fwd_ms": round(stage["ctx_fwd"] + stage["fwd"], 4),
         "bwd_ms": round(sum(stage[k] for k in stage if "bwd" in k), 4),
         "roofline": roofline,
+        "ncopy_flop_ratio": round(fl["ncopy"] / fl["layer"], 3),   # FLOPs of N-copy attention over this layer's
     }
     pre_bytes = 2 * wl.total_resp * H * d * 2 + wl.total_resp * H * 4
     if stage["bwd_pre"] > 0:

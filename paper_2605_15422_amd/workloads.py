@@ -75,6 +75,10 @@ CONFIGS: Dict[str, Shape] = {
     "tab1_n28_p16k": Shape("tab1_n28_p16k", 28, 16384, 2048, 2048, 32, 8, 128, 0, 1102),
     "tab1_n16_p32k": Shape("tab1_n16_p32k", 16, 32768, 2048, 2048, 32, 8, 128, 0, 1103),
     "tab1_n16_p64k": Shape("tab1_n16_p64k", 16, 65536, 2048, 2048, 32, 8, 128, 0, 1104),
+    # the (P, micro-batch) grid of the paper's single-layer comparison (App. "Comparison with Prefix Grouper":
+    # Qwen3-8B dimensions, R ~ U(131, 2048)); bench-only shapes, attention part only
+    **{"grid_p%d_mb%d" % (P, mb): Shape("grid_p%d_mb%d" % (P, mb), mb, P, 131, 2048, 32, 8, 128, 0, 1200 + 10 * i + j)
+       for i, P in enumerate((5059, 8192, 16384, 32768, 65536, 131072)) for j, mb in enumerate((4, 8, 16, 32))},
     # shrunk replicas
     "cfg2_small":  Shape("cfg2_small", 4, 517, 131, 131, 8, 2, 128, 0, 2002),
     "cfg3_small":  Shape("cfg3_small", 6, 509, 17, 260, 8, 2, 128, 0, 2003),
