@@ -33,12 +33,16 @@ struct KCfg {
   static constexpr int QSUB = BM / 32;
   static constexpr int QPITCH = D + 8;
   static constexpr int TPITCH = BM + TPAD;
-  // the exchange buffer of a head-dim split ([NW][16][64] floats) lies over the row-major images, which are
-  // dead by then (one row subtile per step)
-  static_assert(DSPLIT == 1 || (QSUB == 1 && NW * 16 * 64 * 4 <= 2 * BM * QPITCH * 2), "exchange buffer overlay");
+  // The exchange buffer of a head-dim split ([S | dP][NW][16][64] floats) lies over the row-major images, which are
+  // dead by then (one row subtile per step), when it fits there; otherwise it gets LDS of its own.
+  static_assert(DSPLIT == 1 || QSUB == 1, "a head-dim split takes one row subtile per step");
+  static constexpr size_t XCH_BYTES = (size_t)2 * NW * 16 * 64 * 4;
+  static constexpr bool XCH_OVERLAY = XCH_BYTES <= (size_t)2 * BM * QPITCH * 2;
+  static constexpr size_t base_bytes() { return (size_t)(2 * BM * QPITCH + 2 * D * TPITCH) * 2 + 2 * BM * 4; }
   static constexpr size_t smem_bytes() {
-    size_t s = (size_t)(2 * BM * QPITCH + 2 * D * TPITCH) * 2 + 2 * BM * 4;
+    size_t s = base_bytes();
     if (DSPLIT > 1) s += (size_t)KVS * 2 * 64 * 8 * 4;   // bf16 operand images of P and dS per key group
+    if (DSPLIT > 1 && !XCH_OVERLAY) s += XCH_BYTES;
     return s;
   }
 };
@@ -54,8 +58,9 @@ __global__ __launch_bounds__(NW * 64) void dkdv_kernel(const AttnParams p) {
   u16* dOTs = QTs + D * C::TPITCH;                      // [D][TPITCH]
   float* lseL = reinterpret_cast<float*>(dOTs + D * C::TPITCH);  // [BM] LSE * log2(e)
   float* DL = lseL + BM;                                // [BM]
-  float* xch = reinterpret_cast<float*>(smem_raw);      // [NW][16][64] (DSPLIT > 1), over Qs / dOs
   uint32_t* pbuf = reinterpret_cast<uint32_t*>(DL + BM); // [KVS][P | dS][64 lanes][8 words] (DSPLIT > 1)
+  float* xch = C::XCH_OVERLAY ? reinterpret_cast<float*>(smem_raw)      // [S | dP][NW][16][64] (DSPLIT > 1)
+                              : reinterpret_cast<float*>(pbuf + C::KVS * 2 * 64 * 8);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, hi = lane >> 5;
@@ -199,29 +204,32 @@ __global__ __launch_bounds__(NW * 64) void dkdv_kernel(const AttnParams p) {
       bf16x8 pa[2], dsa[2];   // P^T and dS^T of the subtile as MFMA operands (k-steps 0, 1 over the 32 rows)
       if (DSPLIT > 1) {
         // The waves of a key group hold partial S and dP tiles (their part of the head dim).  Each of them sums
-        // RPW of the 16 accumulator registers over the group (S, then dP, through one buffer), evaluates P and dS
+        // RPW of the 16 accumulator registers over the group (S and dP), evaluates P and dS
         // for those, and publishes them as bf16 words of the operand image [lane][8 words]; every wave then
         // reads the whole image: 2 x 16 bytes per operand instead of DSPLIT x 16 partial values, and each
         // exponential is evaluated once per key group.
         constexpr int RPW = 16 / DSPLIT;
         float ssum[RPW], dsum[RPW];
-        __syncthreads();   // every wave has read its row-major operands: the buffer may overwrite them
+        if (C::XCH_OVERLAY) __syncthreads();   // every wave has read its row-major operands: the buffer may overwrite them
+        if (active) {
 #pragma unroll
-        for (int which = 0; which < 2; ++which) {
-          if (which) __syncthreads();
-          if (active) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) xch[(wave * 16 + r) * 64 + lane] = which ? dpv[r] : s[r];
+          for (int r = 0; r < 16; ++r) {
+            xch[(wave * 16 + r) * 64 + lane] = s[r];
+            xch[((NW + wave) * 16 + r) * 64 + lane] = dpv[r];
           }
-          __syncthreads();
-          if (active) {
+        }
+        __syncthreads();
+        if (active) {
 #pragma unroll
-            for (int j = 0; j < RPW; ++j) {
-              float acc = 0.f;
+          for (int j = 0; j < RPW; ++j) {
+            float a0 = 0.f, a1 = 0.f;
 #pragma unroll
-              for (int w2 = 0; w2 < DSPLIT; ++w2) acc += xch[((kvs * DSPLIT + w2) * 16 + dp * RPW + j) * 64 + lane];
-              if (which) dsum[j] = acc; else ssum[j] = acc;
+            for (int w2 = 0; w2 < DSPLIT; ++w2) {
+              a0 += xch[((kvs * DSPLIT + w2) * 16 + dp * RPW + j) * 64 + lane];
+              a1 += xch[((NW + kvs * DSPLIT + w2) * 16 + dp * RPW + j) * 64 + lane];
             }
+            ssum[j] = a0;
+            dsum[j] = a1;
           }
         }
         uint32_t* img = pbuf + kvs * (2 * 64 * 8);
