@@ -177,6 +177,60 @@ def cpu_baseline(wl, max_tokens=9216):
                       "KV head 0 with its %d query heads; algorithmic flops = 14*d*visible pairs" % (S, G)}
 
 
+def time_groups(shape, n_groups, steps):
+    """`n_groups` prompt groups of `shape` (different seeds), one layer pass each: the per-group calls issued
+    eagerly, and the same calls captured once in a HIP graph and replayed (one launch for all groups)."""
+    import torch
+    from paper_2605_15422_amd import binding as B, runner
+    from paper_2605_15422_amd import workloads as W
+    groups = []
+    for g in range(n_groups):
+        sh = W.Shape("%s_g%d" % (shape.name, g), shape.n_seqs, shape.ctx_len, shape.resp_lo, shape.resp_hi,
+                     shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.window, shape.seed + 100 * (g + 1))
+        dg = B.upload(W.make_workload(sh))
+        groups.append((dg, runner.alloc(dg, poison=False)))
+
+    def all_groups():
+        for dg, b in groups:
+            runner.layer_step(dg, b)
+
+    # independent groups on a few streams (default priority): branches of the captured graph that may overlap
+    side = [torch.cuda.Stream() for _ in range(min(4, n_groups))]
+
+    def all_groups_forked():
+        cur = torch.cuda.current_stream()
+        for st in side:
+            st.wait_stream(cur)
+        for i, (dg, b) in enumerate(groups):
+            with torch.cuda.stream(side[i % len(side)]):
+                runner.layer_step(dg, b)
+        for st in side:
+            cur.wait_stream(st)
+
+    all_groups()
+    all_groups_forked()
+    torch.cuda.synchronize()
+    graph, graph_forked = torch.cuda.CUDAGraph(), torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        all_groups()
+    with torch.cuda.graph(graph_forked):
+        all_groups_forked()
+    res = {}
+    for name, fn in (("eager", all_groups), ("eager_streams", all_groups_forked), ("graph", graph.replay),
+                     ("graph_branches", graph_forked.replay)):
+        fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        res[name] = round((time.perf_counter() - t0) * 1e3 / steps, 4)
+    return {"groups": n_groups, **{k + "_ms": v for k, v in res.items()},
+            "what": "wall time per pass over all groups: per-group calls issued one by one on one stream / on %d "
+                    "streams, and one replay of a HIP graph that captured them as a chain / as %d branches"
+                    % (len(side), len(side))}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -186,6 +240,8 @@ def main():
     ap.add_argument("--no-ncopy", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--ncopy-steps", type=int, default=2)
+    ap.add_argument("--graph-groups", type=int, default=0,
+                    help="also time this many prompt groups of the config, eagerly and as one captured graph")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (one GPU per box; no collectives are built); "
@@ -256,6 +312,8 @@ def main():
                         "tflops": round(fl["ncopy"] / (nms * 1e-3) / 1e12, 2), "speedup_dualkv": round(nms / ms, 3),
                         "flop_ratio": round(fl["ncopy"] / fl["layer"], 3),
                         "what": "same kernels on the replicated N x (P+R_i) layout (ctx_len=0), fwd+bwd"}
+    if args.graph_groups > 0:
+        out["multi_group"] = time_groups(shape, args.graph_groups, max(args.steps, 20))
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(out), flush=True)

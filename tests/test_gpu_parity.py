@@ -239,3 +239,69 @@ def test_random_small_shapes():
         print("case random", i, dict(d=d, H=hk * g, Hk=hk, N=n, P=P, lens=lens, win=win, flags=flags), flush=True)
         shape = W.Shape("rnd%d" % i, n, P, 0, 0, hk * g, hk, d, win, seed=9000 + i)
         PU.full_parity(W.make_workload(shape, resp_lens=np.asarray(lens)), flags=flags, verbose=False)
+
+
+def test_prompt_groups_in_one_graph():
+    """Several prompt groups with different P, N and response lengths (Sec. 2.2, "multiple groups"): the per-group
+    calls only enqueue kernels on the caller's stream, so one captured graph replays the whole set with a single
+    launch.  Every replay is checked against the eager result, with eager work and new inputs between replays."""
+    import torch
+    from paper_2605_15422_amd import binding as B, runner
+    specs = [(3, 100, [40, 17, 64], 4, 2, 128), (2, 257, [90, 33], 8, 2, 128), (4, 33, [5, 64, 1, 31], 4, 4, 64)]
+    groups = []
+    for i, (n, P, lens, H, Hk, d) in enumerate(specs):
+        shape = W.Shape("grp%d" % i, n, P, 0, 0, H, Hk, d, 0, seed=7700 + i)
+        dg = B.upload(W.make_workload(shape, resp_lens=np.asarray(lens)))
+        groups.append((dg, runner.alloc(dg)))
+    outs = ("o_c", "lse_c", "o_d", "lse_d", "dq_c", "dq_d", "dk_d", "dv_d", "dk_c1", "dv_c1", "dk_c2", "dv_c2")
+    exact = outs[:8]          # the shared-prompt gradients of tiny groups go through fp32 atomics: order-dependent
+
+    def eager():
+        for dg, b in groups:
+            runner.layer_step(dg, b)
+        torch.cuda.synchronize()
+        return [{k: getattr(b, k).clone() for k in outs} for _, b in groups]
+
+    def poison():
+        for _, b in groups:
+            for k in outs:
+                getattr(b, k).view(torch.int16 if getattr(b, k).dtype == torch.bfloat16 else torch.int32).fill_(-1)
+        torch.cuda.synchronize()
+
+    def check(want, tag):
+        for gi, (_, b) in enumerate(groups):
+            for k in outs:
+                got, ref = getattr(b, k).float(), want[gi][k].float()
+                assert torch.isfinite(got).all(), (tag, gi, k)
+                if k in exact:
+                    assert torch.equal(got, ref), (tag, gi, k)
+                else:
+                    assert (got - ref).norm() <= 1e-2 * ref.norm() + 1e-6, (tag, gi, k)
+
+    want = eager()            # also loads every kernel before the capture
+    chain, branches = torch.cuda.CUDAGraph(), torch.cuda.CUDAGraph()
+    with torch.cuda.graph(chain):
+        for dg, b in groups:
+            runner.layer_step(dg, b)
+    # the groups are independent: one branch per group (streams of default priority) lets them overlap
+    side = [torch.cuda.Stream() for _ in groups]
+    with torch.cuda.graph(branches):
+        cur = torch.cuda.current_stream()
+        for st, (dg, b) in zip(side, groups):
+            st.wait_stream(cur)
+            with torch.cuda.stream(st):
+                runner.layer_step(dg, b)
+        for st in side:
+            cur.wait_stream(st)
+    for rep in range(3):
+        if rep:               # new inputs in the same buffers, eager result first
+            for dg, _ in groups:
+                dg.q_d.copy_(torch.roll(dg.q_d, 1, 0))
+                dg.k_c.copy_(torch.roll(dg.k_c, 1, 0))
+            want = eager()
+        for name, graph in (("chain", chain), ("branches", branches)):
+            print("case graph replay", rep, name, flush=True)
+            poison()
+            graph.replay()
+            torch.cuda.synchronize()
+            check(want, "%s replay %d" % (name, rep))
