@@ -24,7 +24,10 @@
  *   - The caller owns every buffer, including the workspace; the library never
  *     allocates device memory, keeps no mutable global state and never
  *     synchronises: all work is enqueued on `stream` (a hipStream_t passed as
- *     void*; NULL is the default stream).
+ *     void*; NULL is the default stream).  The enqueued work consists of kernel
+ *     launches only (no memset or copy nodes), so the calls may be issued on a
+ *     stream under capture: several prompt groups (Sec. 2.2) are one call
+ *     sequence each, captured once in a HIP graph and replayed with one launch.
  *   - Outputs are fully overwritten.  The only exception are the fp32
  *     accumulators in DUALKV_FLAG_ACCUM_CTX_F32 mode, which are added into.
  *   - Every entry point returns DUALKV_OK or a negative error code; arguments are
