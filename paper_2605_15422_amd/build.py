@@ -14,6 +14,12 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-munsafe-fp-ato
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 
 
+# The generic kernels run four waves of up to 512 registers at some head dims.  There the compiler's default puts MFMA
+# results in the accumulation half of the register file and copies them back and forth for the vector ALU (256 copies
+# per tile in the d = 256 dQ kernel); with the MFMAs in their VGPR form it allocates the two halves itself (8 % faster).
+PER_FILE_FLAGS = {"qstat.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"], "kvstat.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
+
+
 def _hipcc() -> str:
     for c in (os.environ.get("HIPCC"), "/opt/rocm/bin/hipcc", "hipcc"):
         if c and (os.path.isabs(c) and os.path.exists(c) or not os.path.isabs(c)):
@@ -29,7 +35,7 @@ def build(verbose: bool = True, extra_flags=()) -> str:
 
     def compile_one(src):
         obj = os.path.join(objdir, src.replace(".hip", ".o"))
-        cmd = [hipcc, *FLAGS, *extra_flags, "-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [hipcc, *FLAGS, *PER_FILE_FLAGS.get(src, []), *extra_flags, "-c", os.path.join(CSRC, src), "-o", obj]
         r = subprocess.run(cmd, capture_output=True, text=True)
         if r.returncode != 0:
             raise RuntimeError("hipcc failed for %s:\n%s\n%s" % (src, r.stdout, r.stderr))
