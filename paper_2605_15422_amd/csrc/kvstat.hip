@@ -238,7 +238,7 @@ __global__ __launch_bounds__(NW * 64) void dkdv_kernel(const AttnParams p) {
 #pragma unroll
           for (int j = 0; j < RPW; ++j) {
             const int rl = crow(dp * RPW + j, hi);
-            float e = exp2f(ssum[j] * c - lseL[qs * 32 + rl]);
+            float e = __builtin_amdgcn_exp2f(ssum[j] * c - lseL[qs * 32 + rl]);
             if (need_mask) {
               const int row = srow0 + rl;
               bool ok;
@@ -278,7 +278,7 @@ __global__ __launch_bounds__(NW * 64) void dkdv_kernel(const AttnParams p) {
         float pv[16], dsv[16];
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          float e = exp2f(s[r] * c - lr[r]);
+          float e = __builtin_amdgcn_exp2f(s[r] * c - lr[r]);
           if (need_mask) {
             const int row = srow0 + crow(r, hi);
             bool ok;

@@ -180,7 +180,7 @@ __global__ __launch_bounds__(NW * 64) void fwd_kernel(const AttnParams p) {
         // rescale lazily: keep the reference maximum until some row's maximum outgrows it by 2^8
         if (__any(mx > m_ref[qs] + 8.0f)) {
           const float mn = fmaxf(m_ref[qs], mx);
-          const float alpha = exp2f(m_ref[qs] - mn);
+          const float alpha = __builtin_amdgcn_exp2f(m_ref[qs] - mn);
           m_ref[qs] = mn;
           l_sum[qs] *= alpha;
 #pragma unroll
@@ -193,7 +193,7 @@ __global__ __launch_bounds__(NW * 64) void fwd_kernel(const AttnParams p) {
         for (int kv = 0; kv < C::KVSUB; ++kv)
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
-            const float e = exp2f(s[qs][kv][r] * c - m_ref[qs]);
+            const float e = __builtin_amdgcn_exp2f(s[qs][kv][r] * c - m_ref[qs]);
             s[qs][kv][r] = e;
             ls += e;
           }
@@ -404,7 +404,7 @@ __global__ __launch_bounds__(NW * 64) void dq_kernel(const AttnParams p) {
           float dsv[RPW];
 #pragma unroll
           for (int j = 0; j < RPW; ++j) {
-            float e = exp2f(ssum[kv][j] * c - lse2[0]);
+            float e = __builtin_amdgcn_exp2f(ssum[kv][j] * c - lse2[0]);
             if (need) {
               const int key = key0 + kv * 32 + crow(dp * RPW + j, hi);
               if (!visible<LOCAL>(is_ctx, key, row, P, R, W)) e = 0.f;
@@ -426,7 +426,7 @@ __global__ __launch_bounds__(NW * 64) void dq_kernel(const AttnParams p) {
         for (int kv = 0; kv < C::KVSUB; ++kv) {
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
-            float e = exp2f(s[qs][kv][r] * c - lse2[qs]);
+            float e = __builtin_amdgcn_exp2f(s[qs][kv][r] * c - lse2[qs]);
             if (need) {
               const int key = key0 + kv * 32 + crow(r, hi);
               if (!visible<LOCAL>(is_ctx, key, row, P, R, W)) e = 0.f;
