@@ -177,6 +177,39 @@ def cpu_baseline(wl, max_tokens=9216):
                       "KV head 0 with its %d query heads; algorithmic flops = 14*d*visible pairs" % (S, G)}
 
 
+def time_repack(wl, reps=5):
+    """Layout kernels on one (rows, H, d) bf16 tensor: single-prompt packing -> N replicated sequences and back."""
+    import numpy as np
+    import torch
+    from paper_2605_15422_amd import binding as B
+    s = wl.shape
+    N, P, T = s.n_seqs, s.ctx_len, wl.total_resp
+    cu_dev = torch.from_numpy(wl.cu_seqlens.copy()).cuda()
+    packed = torch.cat([B.bf16_from_bits(wl.q_c), B.bf16_from_bits(wl.q_d)], dim=0)
+    row_bytes = packed.shape[1] * packed.shape[2] * 2
+    rows_rep = N * P + T
+    standard = torch.empty((rows_rep,) + tuple(packed.shape[1:]), dtype=torch.bfloat16, device="cuda")
+    back = torch.empty_like(packed)
+    pos = torch.empty(P + T, dtype=torch.int32, device="cuda")
+    res = {}
+    for name, fn, nbytes in (
+            ("replicate", lambda: B.dualkv_replicate(N, P, T, cu_dev, row_bytes, packed, standard), 2 * rows_rep * row_bytes),
+            ("repack", lambda: B.dualkv_repack(N, P, T, cu_dev, row_bytes, standard, back, pos), 2 * (P + T) * row_bytes)):
+        fn()
+        ev = _events(2)
+        ev[0].record()
+        for _ in range(reps):
+            fn()
+        ev[1].record()
+        torch.cuda.synchronize()
+        ms = ev[0].elapsed_time(ev[1]) / reps
+        res[name] = {"ms": round(ms, 4), "gbs": round(nbytes / (ms * 1e-3) / 1e9, 1)}
+    assert torch.equal(back, packed)
+    res["what"] = ("one (rows, H, d) bf16 tensor, %d B per row: %d packed rows <-> %d replicated rows; GB/s counts bytes "
+                   "read + written by the gather" % (row_bytes, P + T, rows_rep))
+    return res
+
+
 def time_groups(shape, n_groups, steps):
     """`n_groups` prompt groups of `shape` (different seeds), one layer pass each: the per-group calls issued
     eagerly, and the same calls captured once in a HIP graph and replayed (one launch for all groups)."""
@@ -312,6 +345,8 @@ def main():
                         "tflops": round(fl["ncopy"] / (nms * 1e-3) / 1e12, 2), "speedup_dualkv": round(nms / ms, 3),
                         "flop_ratio": round(fl["ncopy"] / fl["layer"], 3),
                         "what": "same kernels on the replicated N x (P+R_i) layout (ctx_len=0), fwd+bwd"}
+    if not args.no_ncopy:
+        out["layout_kernels"] = time_repack(wl)
     if args.graph_groups > 0:
         out["multi_group"] = time_groups(shape, args.graph_groups, max(args.steps, 20))
     if not args.no_cpu:
