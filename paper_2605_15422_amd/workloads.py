@@ -79,6 +79,10 @@ CONFIGS: Dict[str, Shape] = {
     # Qwen3-8B dimensions, R ~ U(131, 2048)); bench-only shapes, attention part only
     **{"grid_p%d_mb%d" % (P, mb): Shape("grid_p%d_mb%d" % (P, mb), mb, P, 131, 2048, 32, 8, 128, 0, 1200 + 10 * i + j)
        for i, P in enumerate((5059, 8192, 16384, 32768, 65536, 131072)) for j, mb in enumerate((4, 8, 16, 32))},
+    # one mid-size shape per remaining head dim of the supported set (bench-only)
+    "dim_d64":  Shape("dim_d64", 8, 16384, 2048, 2048, 32, 8, 64, 0, 1301),
+    "dim_d96":  Shape("dim_d96", 8, 16384, 2048, 2048, 16, 4, 96, 0, 1302),
+    "dim_d192": Shape("dim_d192", 8, 16384, 2048, 2048, 12, 4, 192, 0, 1303),
     # shrunk replicas
     "cfg2_small":  Shape("cfg2_small", 4, 517, 131, 131, 8, 2, 128, 0, 2002),
     "cfg3_small":  Shape("cfg3_small", 6, 509, 17, 260, 8, 2, 128, 0, 2003),
