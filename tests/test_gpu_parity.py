@@ -42,6 +42,10 @@ EDGE = [
     ("d96_win", 2, 130, [90, 33], 2, 2, 96, 40),
     ("d192", 3, 200, [33, 130, 64], 6, 2, 192, 0),
     ("d192_win", 2, 140, [64, 90], 4, 2, 192, 50),
+    ("all_empty", 2, 64, [0, 0], 4, 2, 128, 0),
+    ("all_empty_d256", 3, 33, [0, 0, 0], 2, 1, 256, 0),
+    ("p1_r1", 1, 1, [1], 1, 1, 64, 0),
+    ("p0_r1", 1, 0, [1], 2, 2, 128, 0),
 ]
 
 
