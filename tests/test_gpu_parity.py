@@ -46,6 +46,8 @@ EDGE = [
     ("all_empty_d256", 3, 33, [0, 0, 0], 2, 1, 256, 0),
     ("p1_r1", 1, 1, [1], 1, 1, 64, 0),
     ("p0_r1", 1, 0, [1], 2, 2, 128, 0),
+    ("many_seqs", 96, 40, [(7 * i) % 5 for i in range(96)], 4, 2, 128, 0),
+    ("many_seqs_d256_win", 48, 70, [(5 * i) % 9 for i in range(48)], 2, 1, 256, 6),
 ]
 
 
