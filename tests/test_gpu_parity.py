@@ -60,15 +60,17 @@ def test_edge_cases(case):
     PU.full_parity(wl)
 
 
-def test_strided_views_of_one_packed_qkv_buffer():
-    """Zero-copy prompt/response views of one packed (T, H+2Hk, d) buffer (App. A.3 "QKV split")."""
+@pytest.mark.parametrize("d", [128, 96, 256, 512])
+def test_strided_views_of_one_packed_qkv_buffer(d):
+    """Zero-copy prompt/response views of one packed (T, H+2Hk, d) buffer (App. A.3 "QKV split"), through the tuned
+    (d = 128) and the generic kernels."""
     import torch
     from paper_2605_15422_amd import binding as B, runner
-    print("case packed_qkv", flush=True)
-    shape = W.Shape("packed_qkv", 3, 90, 0, 0, 4, 2, 128, 0, seed=77)
+    print("case packed_qkv", d, flush=True)
+    shape = W.Shape("packed_qkv", 3, 90, 0, 0, 4, 2, d, 0, seed=77)
     wl = W.make_workload(shape, resp_lens=np.asarray([40, 70, 9]))
     dg = B.upload(wl)
-    P, T, H, Hk, d = 90, wl.total_resp, 4, 2, 128
+    P, T, H, Hk = 90, wl.total_resp, 4, 2
     packed = torch.empty((P + T, H + 2 * Hk, d), dtype=torch.bfloat16, device="cuda")
     packed[:P, :H] = dg.q_c
     packed[:P, H:H + Hk] = dg.k_c
@@ -90,6 +92,10 @@ def test_strided_views_of_one_packed_qkv_buffer():
     torch.cuda.synchronize()
     for n in ("o_c", "o_d", "lse_c", "lse_d", "dq_c", "dq_d", "dk_c1", "dv_c1", "dk_c2", "dv_c2", "dk_d", "dv_d"):
         a, c = getattr(b1, n), getattr(b2, n)
+        if n.startswith(("dk_c", "dv_c")):
+            # shared-prompt gradients of a small group are summed with fp32 atomics: equal up to the order of the sum
+            assert (a.float() - c.float()).norm() <= 1e-2 * a.float().norm(), n
+            continue
         assert torch.equal(a.view(torch.int16) if a.dtype == torch.bfloat16 else a,
                            c.contiguous().view(torch.int16) if c.dtype == torch.bfloat16 else c), n
 
