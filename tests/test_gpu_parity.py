@@ -156,7 +156,7 @@ def test_label_map(P, lens):
     B.dualkv_label_map(N, P, T, cu_dev, torch.from_numpy(nxt).cuda() if P + T else None, None)
 
 
-@pytest.mark.parametrize("name", ["cfg2_small", "cfg3_small", "cfg5b_small"])
+@pytest.mark.parametrize("name", ["cfg2_small", "cfg3_small", "cfg5a_small", "cfg5b_small"])
 def test_run_to_run_determinism(name):
     """Everything that is not summed with atomics is bitwise reproducible from run to run (different LDS and
     register garbage, other kernels in between): catches reads of stale or not-yet-written data that stay
