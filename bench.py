@@ -205,6 +205,21 @@ def time_repack(wl, reps=5):
         ms = ev[0].elapsed_time(ev[1]) / reps
         res[name] = {"ms": round(ms, 4), "gbs": round(nbytes / (ms * 1e-3) / 1e9, 1)}
     assert torch.equal(back, packed)
+    if P > 0:
+        # fp32 -> bf16 cast of the shared-prompt gradients (Alg. 2): 2 tensors x (4 B read + 2 B written) per element
+        Hk, d = s.n_kv_heads, s.head_dim
+        shp = B.make_shape(N, P, T, wl.max_resp, s.n_q_heads, Hk, d, s.window, wl.scale, 0)
+        acc = [torch.randn((P, Hk, d), dtype=torch.float32, device="cuda") for _ in range(2)]
+        outb = [torch.empty((P, Hk, d), dtype=torch.bfloat16, device="cuda") for _ in range(2)]
+        B.dualkv_finalize_ctx_grads(shp, acc[0], acc[1], outb[0], outb[1])
+        ev = _events(2)
+        ev[0].record()
+        for _ in range(reps):
+            B.dualkv_finalize_ctx_grads(shp, acc[0], acc[1], outb[0], outb[1])
+        ev[1].record()
+        torch.cuda.synchronize()
+        ms = ev[0].elapsed_time(ev[1]) / reps
+        res["finalize_ctx_grads"] = {"ms": round(ms, 4), "gbs": round(2 * P * Hk * d * 6 / (ms * 1e-3) / 1e9, 1)}
     res["what"] = ("one (rows, H, d) bf16 tensor, %d B per row: %d packed rows <-> %d replicated rows; GB/s counts bytes "
                    "read + written by the gather" % (row_bytes, P + T, rows_rep))
     return res
