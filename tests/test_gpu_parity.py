@@ -357,3 +357,34 @@ def test_largest_token_stride(d):
             assert (a - c).norm() <= 1e-2 * a.norm(), n    # fp32 atomics: equal up to the order of the sum
         else:
             assert torch.equal(a, c), n
+
+
+@pytest.mark.parametrize("d", [128, 256])
+def test_head_major_views(d):
+    """Every tensor stored head-major, (heads, rows, d), and passed as a (rows, heads, d) view: token stride d,
+    head stride rows * d."""
+    import torch
+    from paper_2605_15422_amd import binding as B, runner
+    print("case head_major", d, flush=True)
+    shape = W.Shape("head_major", 3, 70, 0, 0, 4, 2, d, 0, seed=4300 + d)
+    wl = W.make_workload(shape, resp_lens=np.asarray([40, 0, 65]))
+    dg = B.upload(wl)
+
+    def hm(t):   # same values, head-major storage
+        return t.permute(1, 0, 2).contiguous().permute(1, 0, 2)
+
+    dg2 = B.DeviceGroup(dg.shape_c, hm(dg.q_c), hm(dg.k_c), hm(dg.v_c), hm(dg.q_d), hm(dg.k_d), hm(dg.v_d),
+                        hm(dg.do_c), hm(dg.do_d), dg.cu_dev, dg.cu_host)
+    b1 = runner.alloc(dg)
+    runner.layer_step(dg, b1)
+    b2 = runner.alloc(dg)
+    for n in ("o_c", "o_d", "dq_c", "dq_d", "dk_d", "dv_d", "dk_c1", "dv_c1", "dk_c2", "dv_c2"):
+        setattr(b2, n, hm(getattr(b2, n)))
+    runner.layer_step(dg2, b2)
+    torch.cuda.synchronize()
+    for n in ("o_c", "o_d", "lse_c", "lse_d", "dq_c", "dq_d", "dk_d", "dv_d", "dk_c1", "dv_c1", "dk_c2", "dv_c2"):
+        a, c = getattr(b1, n).float(), getattr(b2, n).float()
+        if n.startswith(("dk_c", "dv_c")):
+            assert (a - c).norm() <= 1e-2 * a.norm(), n    # fp32 atomics: equal up to the order of the sum
+        else:
+            assert torch.equal(a, c), n
