@@ -121,7 +121,9 @@ int dualkv_ctx_bwd(const dualkv_shape* shape, dualkv_tin do_c, dualkv_tin o_c, c
  * k_d, v_d: (total_resp, H_k, d); cu_seqlens_dev: (N+1) int32 offsets of the responses in the packed
  * response tensors (one array serves q and k_d, App. E); lse_d: (H, total_resp) fp32.
  * cu_seqlens_host (optional, may be NULL): host copy of the same array, used only to validate it
- * (monotone, last == total_resp) before launch. */
+ * (monotone, last == total_resp) before launch.  The device array itself cannot be checked without a
+ * synchronisation: it must start at 0, be non-decreasing, end at total_resp and have no response longer than
+ * max_resp; the kernels index the response tensors with it and do not test it. */
 int dualkv_fwd(const dualkv_shape* shape, dualkv_tin q_d, dualkv_tin k_c, dualkv_tin v_c,
                dualkv_tin k_d, dualkv_tin v_d,
                const int32_t* cu_seqlens_dev, const int32_t* cu_seqlens_host,
