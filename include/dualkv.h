@@ -50,7 +50,7 @@ extern "C" {
 #define DUALKV_OK             0
 #define DUALKV_E_INVALID     (-1)  /* NULL pointer, negative size, H % H_k != 0, bad cu_seqlens ... */
 #define DUALKV_E_UNSUPPORTED (-2)  /* head_dim not in {64,96,128,192,256,512}; window with head_dim 512;
-                                      tok_stride > DUALKV_MAX_TOK_STRIDE                                   */
+                                      tok_stride > DUALKV_MAX_TOK_STRIDE; rows * H >= 2^30 at head_dim 64/128 */
 #define DUALKV_E_WORKSPACE   (-3)  /* workspace pointer NULL or smaller than dualkv_workspace_bytes  */
 #define DUALKV_E_ALIGN       (-4)  /* pointer not 16-byte aligned or stride not a multiple of 8      */
 #define DUALKV_E_HIP         (-5)  /* a HIP runtime call (launch) failed                             */
@@ -62,7 +62,7 @@ extern "C" {
 
 /* dK_c / dV_c of this call are ADDED into caller-provided fp32 buffers (P, H_k, d), contiguous,
  * instead of being written as bf16; both backward calls may add into the same buffers so that the
- * Call-1 + Call-2 sum (Eq. "dkc-total") is formed in fp32 and cast once by
+ * Call-1 + Call-2 sum (Eq. 6; App. A.4, total gradient of the shared keys and values) is formed in fp32 and cast once by
  * dualkv_finalize_ctx_grads.  The caller zeroes the buffers before the first call. */
 #define DUALKV_FLAG_ACCUM_CTX_F32 1u
 /* Backward calls only: run a subset of the three backward stages (preprocess: D = rowsum(dO*O) and
@@ -129,7 +129,8 @@ int dualkv_fwd(const dualkv_shape* shape, dualkv_tin q_d, dualkv_tin k_c, dualkv
                const int32_t* cu_seqlens_dev, const int32_t* cu_seqlens_host,
                dualkv_tout o_d, float* lse_d, void* workspace, size_t workspace_bytes, void* stream);
 
-/* Call 2 backward (Alg. 1 + Alg. 2, Eq. "dkc-dec"/"dvc-dec"): returns dQ_d (total_resp,H,d),
+/* Call 2 backward (Alg. 1 + Alg. 2; App. A.4 "Call 2 backward", the response-branch terms of dK_c and
+ * dV_c): returns dQ_d (total_resp,H,d),
  * dK_d, dV_d (total_resp,H_k,d) and the Call-2 terms of dK_c, dV_c (P,H_k,d): the sum over all N
  * sequences and the H/H_k heads of each group, accumulated in fp32 and cast to bf16 once, or added
  * into dk_c_acc32 / dv_c_acc32 under DUALKV_FLAG_ACCUM_CTX_F32. */

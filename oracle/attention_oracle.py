@@ -30,8 +30,9 @@ Conventions fixed here where the paper is silent:
 Pins (tests/test_oracle_*.py): closed forms (zero keys -> running mean and
 log-count, two-key logistic, key-shift invariance), central finite differences
 of all gradients, an autograd evaluation of the same loss, explicit-loop
-evaluation of Eq. 4 in the single-prompt layout, and finite differences with
-respect to the *shared* K_c/V_c.
+evaluation of Eq. 4 in the single-prompt layout, finite differences with
+respect to the *shared* K_c/V_c, the row samplers' O / LSE / dQ against the dense
+pass, and hand-written examples of the two packings and their position ids.
 """
 from __future__ import annotations
 
@@ -375,3 +376,48 @@ def next_token_pairs_replicated(P, cu):
             pairs.add((packed[s], packed[s + 1]))
     return pairs
 
+
+
+# --------------------------------------------------------------------------
+# the two packings as data movement (Eq. 1 <-> Eq. 5) and their position ids (App. A.2)
+# --------------------------------------------------------------------------
+def replicated_layout(P, cu, x_c, x_d):
+    """Standard packing (Eq. 1) of per-token records: [prompt, resp_1 | prompt, resp_2 | ...].
+
+    x_c: (P, ...) prompt records, x_d: (T, ...) packed response records, cu: (N+1,) response offsets.
+    Returns (x_rep, cu_rep): sequence i occupies rows cu_rep[i]:cu_rep[i+1] = its own prompt copy (P rows)
+    followed by its R_i response rows.
+    """
+    n = len(cu) - 1
+    parts = []
+    cu_rep = np.zeros(n + 1, dtype=np.int32)
+    for i in range(n):
+        parts.append(x_c[:P])
+        parts.append(x_d[cu[i]:cu[i + 1]])
+        cu_rep[i + 1] = cu_rep[i] + P + (cu[i + 1] - cu[i])
+    return np.concatenate(parts, axis=0), cu_rep
+
+
+def single_prompt_layout(P, cu, x_rep):
+    """Inverse of replicated_layout (Eq. 5): [prompt | resp_1 | ... | resp_N], the prompt taken from
+    sequence 0's copy."""
+    n = len(cu) - 1
+    parts = [x_rep[:P]]
+    off = 0
+    for i in range(n):
+        R = int(cu[i + 1] - cu[i])
+        parts.append(x_rep[off + P:off + P + R])
+        off += P + R
+    return np.concatenate(parts, axis=0)
+
+
+def position_ids_replicated(P, cu):
+    """Logical position of every row of the standard packing: 0 .. P+R_i-1 inside each sequence."""
+    return np.concatenate([np.arange(P + int(cu[i + 1] - cu[i])) for i in range(len(cu) - 1)]).astype(np.int64)
+
+
+def position_ids_single_prompt(P, cu):
+    """Logical position of every row of the single-prompt packing: prompt row j -> j, row r of any
+    response -> P + r (the position it has in its own replica; App. A.2)."""
+    return np.concatenate([np.arange(P)] +
+                          [P + np.arange(int(cu[i + 1] - cu[i])) for i in range(len(cu) - 1)]).astype(np.int64)

@@ -27,6 +27,10 @@ int check_shape(const dualkv_shape* s, bool ctx_call) {
   const int d = s->head_dim;
   if (d != 64 && d != 96 && d != 128 && d != 192 && d != 256 && d != 512) return DUALKV_E_UNSUPPORTED;
   if (s->window > 0 && d == 512) return DUALKV_E_UNSUPPORTED;
+  // the backward statistics (D, then LSE in base-2 units) are two (H, rows) fp32 arrays carved from one workspace;
+  // the d = 64 / 128 dK/dV kernel addresses the second as the first plus a 32-bit byte offset
+  const int64_t rows = ctx_call ? s->ctx_len : s->total_resp;
+  if ((d == 64 || d == 128) && rows * s->n_q_heads >= (int64_t(1) << 30) - 64) return DUALKV_E_UNSUPPORTED;
   return DUALKV_OK;
 }
 
@@ -103,11 +107,7 @@ hipError_t run_dq(const AttnParams& p, int d, hipStream_t st) {
   return dkv::launch_dq(p, d, st);
 }
 hipError_t run_dkdv(const AttnParams& p, int d, hipStream_t st) {
-  if (d == 64 || d == 128) {
-    // the producer/consumer kernel needs the two statistics arrays within 4 GB of each other
-    const bool near = reinterpret_cast<uintptr_t>(p.lse2) - reinterpret_cast<uintptr_t>(p.dvec) < (1ull << 32);
-    return near ? dkv::launch_dkdv4(p, d, st) : dkv::launch_dkdv3(p, d, st);
-  }
+  if (d == 64 || d == 128) return dkv::launch_dkdv4(p, d, st);
   return dkv::launch_dkdv(p, d, st);
 }
 

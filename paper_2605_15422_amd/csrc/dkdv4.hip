@@ -542,8 +542,7 @@ static hipError_t launch_dkdv4_t(AttnParams p, hipStream_t st) {
     return hipErrorInvalidValue;
   const size_t smem = 6 * (2 * 32 * 2 * D + 256 + 64) + 2 * 16384;
   auto kern = dkdv4_kernel<D, LOCAL>;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+  hipError_t e = ensure_dynamic_lds<dkdv4_kernel<D, LOCAL>>(smem);
   if (e != hipSuccess) return e;
   const int64_t nblk = (int64_t)p.n_ctx_tiles * p.Hk * p.n_split + (int64_t)p.n_seqs * p.n_dec_tiles * p.Hk;
   if (nblk == 0) return hipSuccess;

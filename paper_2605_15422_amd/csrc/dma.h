@@ -13,19 +13,23 @@
 
 namespace dkv {
 
+// Both loads write M0 (the LDS base of the instruction) and say so in their clobber lists: the compiler reserves M0
+// and sets it itself right before each of its own uses, but its passes that move or merge M0 initialisations look
+// for definitions in between, and an asm statement is one only if it is declared (the compiler's warning about
+// reserved registers in clobber lists is switched off for this library).
 // 64 lanes x 16 bytes: global address = sbase + voff (per lane), LDS address = lds_addr + 16 * lane.
 __device__ __forceinline__ void dma16(const void* sbase, uint32_t voff, uint32_t lds_addr) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                :
                : "s"(lds_addr), "v"(voff), "s"(sbase)
-               : "memory");
+               : "memory", "m0");
 }
 // 64 lanes x 4 bytes: global address = sbase + voff (per lane), LDS address = lds_addr + 4 * lane.
 __device__ __forceinline__ void dma4(const void* sbase, uint32_t voff, uint32_t lds_addr) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
                :
                : "s"(lds_addr), "v"(voff), "s"(sbase)
-               : "memory");
+               : "memory", "m0");
 }
 template <int N>
 __device__ __forceinline__ void wait_vm() {

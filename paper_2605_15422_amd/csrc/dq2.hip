@@ -226,8 +226,7 @@ static hipError_t launch_dq2_t(AttnParams p, hipStream_t st) {
   fill_packing(p, 8);
   const size_t smem = 3 * 2 * 64 * 2 * D;
   auto kern = dq2_kernel<D, LOCAL>;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+  hipError_t e = ensure_dynamic_lds<dq2_kernel<D, LOCAL>>(smem);
   if (e != hipSuccess) return e;
   const int64_t nblk = (int64_t)p.n_seqs * p.MB * p.HC * p.Hk;
   if (nblk == 0) return hipSuccess;

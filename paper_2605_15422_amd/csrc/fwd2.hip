@@ -24,13 +24,11 @@
 
 namespace dkv {
 
-#ifndef DKV_FWD_NW
-#define DKV_FWD_NW 8
-#endif
+constexpr int kFwdWaves = 8;   // the K / V loader split below assumes eight waves
 
 template <int D>
 struct F2Cfg {
-  static constexpr int NW = DKV_FWD_NW, NT = NW * 64, BN = 64;
+  static constexpr int NW = kFwdWaves, NT = NW * 64, BN = 64;
   static constexpr int KS = D / 16, DSUB = D / 32;
   static constexpr int RB = 2 * D;                 // row bytes
   static constexpr int CPR = D / 8;                // 16-byte chunks per row
@@ -41,7 +39,7 @@ struct F2Cfg {
 };
 
 template <int D, bool LOCAL>
-__global__ __launch_bounds__(DKV_FWD_NW * 64) void fwd2_kernel(const AttnParams p) {
+__global__ __launch_bounds__(kFwdWaves * 64) void fwd2_kernel(const AttnParams p) {
   using C = F2Cfg<D>;
   constexpr int BN = C::BN;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];   // K ring [4 tiles] | V ring [4 tiles]
@@ -388,8 +386,7 @@ static hipError_t launch_fwd2_t(AttnParams p, hipStream_t st) {
   fill_packing(p, C::NW);
   const size_t smem = 4 * 2 * C::TILE_BYTES;
   auto kern = fwd2_kernel<D, LOCAL>;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+  hipError_t e = ensure_dynamic_lds<fwd2_kernel<D, LOCAL>>(smem);
   if (e != hipSuccess) return e;
   const int64_t nblk = (int64_t)p.n_seqs * p.MB * p.HC * p.Hk;
   if (nblk == 0) return hipSuccess;

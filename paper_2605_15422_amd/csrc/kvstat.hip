@@ -347,8 +347,7 @@ static hipError_t launch_dkdv_t(AttnParams p, hipStream_t st) {
   if (p.n_split < 1) p.n_split = 1;
   const size_t smem = C::smem_bytes();
   auto kern = dkdv_kernel<D, DSPLIT, NW, BM, TPAD, LOCAL>;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+  hipError_t e = ensure_dynamic_lds<dkdv_kernel<D, DSPLIT, NW, BM, TPAD, LOCAL>>(smem);
   if (e != hipSuccess) return e;
   const int64_t nblk = (int64_t)p.n_ctx_tiles * p.Hk * p.n_split + (int64_t)p.n_seqs * p.n_dec_tiles * p.Hk;
   if (nblk == 0) return hipSuccess;

@@ -12,7 +12,6 @@ hipError_t launch_dq(const AttnParams& p, int head_dim, hipStream_t st);
 hipError_t launch_dkdv(const AttnParams& p, int head_dim, hipStream_t st);
 // tuned backward kernels for head dims 64 / 128
 hipError_t launch_dq2(const AttnParams& p, int head_dim, hipStream_t st);
-hipError_t launch_dkdv3(const AttnParams& p, int head_dim, hipStream_t st);
 hipError_t launch_dkdv4(const AttnParams& p, int head_dim, hipStream_t st);
 // key tile (rows of K/V owned by one workgroup) of the dK/dV kernel for a head dim
 int dkdv_key_tile(int head_dim);
@@ -26,5 +25,14 @@ hipError_t launch_rows_copy(bool to_packed, int n_seqs, int ctx_len, int total_r
                             int64_t row_bytes, const void* src, void* dst, int32_t* pos_ids, hipStream_t st);
 hipError_t launch_label_map(int n_seqs, int ctx_len, int total_resp, const int32_t* cu, int32_t* next_index,
                             int32_t* first_token_index, hipStream_t st);
+
+// Raises the dynamic-LDS limit of a kernel instantiation once per process (a host API call; not repeated on
+// every launch, so that nothing but kernel launches is issued on a stream under capture after the first use).
+template <auto Kern>
+inline hipError_t ensure_dynamic_lds(size_t bytes) {
+  static hipError_t once = hipFuncSetAttribute(reinterpret_cast<const void*>(Kern),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+  return once;
+}
 
 }  // namespace dkv

@@ -494,8 +494,7 @@ static hipError_t launch_fwd_t(AttnParams p, hipStream_t st) {
   size_t smem = (size_t)(BN * C::KPITCH + D * C::TPITCH) * 2;
   if (DSPLIT > 1) smem += (size_t)C::NW * C::KVSUB * 16 * 64 * 4;
   auto kern = fwd_kernel<D, DSPLIT, QSUB, BN, NW, LOCAL>;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+  hipError_t e = ensure_dynamic_lds<fwd_kernel<D, DSPLIT, QSUB, BN, NW, LOCAL>>(smem);
   if (e != hipSuccess) return e;
   const int64_t nblk = (int64_t)p.n_seqs * p.MB * p.HC * p.Hk;
   if (nblk == 0) return hipSuccess;
@@ -510,8 +509,7 @@ static hipError_t launch_dq_t(AttnParams p, hipStream_t st) {
   size_t smem = (size_t)(2 * BN * C::KPITCH + D * C::TPITCH) * 2;
   if (DSPLIT > 1) smem += (size_t)C::NW * C::KVSUB * 16 * 64 * 4 + (size_t)C::RG * C::KVSUB * 64 * 8 * 4;
   auto kern = dq_kernel<D, DSPLIT, QSUB, BN, NW, LOCAL>;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+  hipError_t e = ensure_dynamic_lds<dq_kernel<D, DSPLIT, QSUB, BN, NW, LOCAL>>(smem);
   if (e != hipSuccess) return e;
   const int64_t nblk = (int64_t)p.n_seqs * p.MB * p.HC * p.Hk;
   if (nblk == 0) return hipSuccess;

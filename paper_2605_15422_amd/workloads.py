@@ -169,19 +169,3 @@ def make_workload(shape: Shape, resp_lens: Optional[np.ndarray] = None,
         do_c=_normal_bf16(s, 7, (P, H, d)),
         do_d=_normal_bf16(s, 8, (T, H, d)),
     )
-
-
-def replicated_layout(P: int, cu: np.ndarray, x_c: np.ndarray, x_d: np.ndarray):
-    """Standard packing (Eq. 1): [prompt, resp_1 | prompt, resp_2 | ...].
-
-    Pure data movement: returns (x_rep, cu_rep) where sequence i occupies rows
-    cu_rep[i]:cu_rep[i+1] = P + R_i rows.
-    """
-    n = len(cu) - 1
-    parts = []
-    cu_rep = np.zeros(n + 1, dtype=np.int32)
-    for i in range(n):
-        parts.append(x_c[:P])
-        parts.append(x_d[cu[i]:cu[i + 1]])
-        cu_rep[i + 1] = cu_rep[i] + P + (cu[i + 1] - cu[i])
-    return np.concatenate(parts, axis=0), cu_rep

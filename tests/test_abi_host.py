@@ -46,6 +46,11 @@ def test_argument_validation_before_launch():
     assert ws(n_seqs=0)[0] == B.E_INVALID
     assert ws(ctx_len=-1)[0] == B.E_INVALID
     assert ws(max_resp=7)[0] == B.E_INVALID
+    # head dims 64 / 128: the two (H, rows) fp32 statistics arrays of the backward must lie within 4 GB
+    big = dict(total_resp=1 << 25, max_resp=1 << 25, n_q_heads=32, n_kv_heads=8)
+    assert ws(**big)[0] == B.E_UNSUPPORTED
+    assert ws(**big, head_dim=256)[0] == B.OK
+    assert ws(**{**big, "total_resp": (1 << 25) - 64, "max_resp": 1 << 20})[0] == B.OK
     s = B.make_shape(**ok)
     assert B.lib.dualkv_workspace_bytes(C.byref(s), 9, C.byref(C.c_size_t())) == B.E_INVALID
     assert B.lib.dualkv_workspace_bytes(None, B.OP_BWD, C.byref(C.c_size_t())) == B.E_INVALID

@@ -101,7 +101,10 @@ def test_strided_views_of_one_packed_qkv_buffer(d):
 
 
 def test_layout_kernels():
+    """Repack / replicate (Eq. 1 <-> Eq. 5) and the position ids (App. A.2), bit for bit against the oracle's
+    packings (pinned by a hand-written example in tests/test_oracle_pins.py)."""
     import torch
+    from oracle import attention_oracle as orc
     from paper_2605_15422_amd import binding as B
     print("case layout", flush=True)
     rng = np.random.default_rng(5)
@@ -114,21 +117,20 @@ def test_layout_kernels():
         n16 = row_bytes // 2
         x_c = rng.integers(0, 65535, size=(P, n16)).astype(np.uint16)
         x_d = rng.integers(0, 65535, size=(T, n16)).astype(np.uint16)
-        std, cu_rep = W.replicated_layout(P, cu, x_c, x_d)
+        std, cu_rep = orc.replicated_layout(P, cu, x_c, x_d)
         cu_dev = torch.from_numpy(cu).cuda()
         packed = torch.from_numpy(np.concatenate([x_c, x_d]).view(np.int16)).cuda()
         out = torch.zeros((N * P + T, n16), dtype=torch.int16, device="cuda")
         pos = torch.full((N * P + T,), -1, dtype=torch.int32, device="cuda")
         B.dualkv_replicate(N, P, T, cu_dev, row_bytes, packed, out, pos)
         assert np.array_equal(out.cpu().numpy().view(np.uint16), std)
-        want_pos = np.concatenate([np.arange(P + l) for l in lens])
-        assert np.array_equal(pos.cpu().numpy(), want_pos)
+        assert np.array_equal(pos.cpu().numpy(), orc.position_ids_replicated(P, cu))
         back = torch.zeros((P + T, n16), dtype=torch.int16, device="cuda")
         pos2 = torch.full((P + T,), -1, dtype=torch.int32, device="cuda")
         B.dualkv_repack(N, P, T, cu_dev, row_bytes, out, back, pos2)
+        assert np.array_equal(back.cpu().numpy().view(np.uint16), orc.single_prompt_layout(P, cu, std))
         assert torch.equal(back, packed)
-        want2 = np.concatenate([np.arange(P)] + [P + np.arange(l) for l in lens])
-        assert np.array_equal(pos2.cpu().numpy(), want2)
+        assert np.array_equal(pos2.cpu().numpy(), orc.position_ids_single_prompt(P, cu))
 
 
 @pytest.mark.parametrize("P,lens", [(37, [5, 0, 19, 8]), (1, [1]), (0, [4, 2]), (300, [0, 0, 700, 1, 64]), (5, [0])])
@@ -208,26 +210,26 @@ def test_growing_scores_exercise_the_lazy_rescale(d):
         lo, hi = int(wl.cu_seqlens[i]), int(wl.cu_seqlens[i + 1])
         ramp_d[lo:hi] = 0.5 + 1.5 * np.arange(hi - lo) / max(1, hi - lo - 1)
     wl.k_d = scaled(wl.k_d, ramp_d[:, None, None])
+    # O and LSE to the stated tolerances; the inputs are four times the usual size and so are the bf16 rounding errors
+    # of the dS operands, so every gradient element is held to the derived rounding bound (no fixed allowance)
+    from oracle import rounding_bound as rb
     x = PU.oracle_inputs(wl)
-    ref = PU.orc.dualkv_reference(x["q_c"], x["k_c"], x["v_c"], x["q_d"], x["k_d"], x["v_d"], wl.cu_seqlens, wl.scale,
-                                  x["do_c"], x["do_d"], wl.shape.window)
+    bnd, ref = rb.dualkv_bounds(x["q_c"], x["k_c"], x["v_c"], x["q_d"], x["k_d"], x["v_d"], wl.cu_seqlens, wl.scale,
+                                x["do_c"], x["do_d"], wl.shape.window)
     dg, b = PU.run_hip_layer(wl)
     rep = []
-    PU.compare("O_c", PU.to_f64(b.o_c), ref["o_c"], rep)
-    PU.compare_lse("LSE_c", PU.to_f64(b.lse_c), ref["lse_c"], rep)
-    PU.compare("O_d", PU.to_f64(b.o_d), ref["o_d"], rep)
-    PU.compare_lse("LSE_d", PU.to_f64(b.lse_d), ref["lse_d"], rep)
-    # the inputs are four times the usual size here, and so are the bf16 rounding errors of the dS operands: the
-    # gradients are held to the relative bound only
-    for name, got, want in (("dQ_d", b.dq_d, ref["call2"]["dq_d"]), ("dK_d", b.dk_d, ref["call2"]["dk_d"]),
-                            ("dV_d", b.dv_d, ref["call2"]["dv_d"]), ("dQ_c", b.dq_c, ref["call1"]["dq_c"]),
-                            ("dK_c(2)", b.dk_c2, ref["call2"]["dk_c"]), ("dV_c(2)", b.dv_c2, ref["call2"]["dv_c"])):
-        g = PU.to_f64(got)
-        assert np.isfinite(g).all(), name
-        rel = float(np.linalg.norm(g - want) / np.linalg.norm(want))
-        rep.append("%-8s relL2=%.3e" % (name, rel))
-        assert rel <= PU.REL_L2, (name, rel)
-    print("\n  " + "\n  ".join(rep), flush=True)
+    try:
+        PU.compare("O_c", PU.to_f64(b.o_c), ref["o_c"], rep)
+        PU.compare_lse("LSE_c", PU.to_f64(b.lse_c), ref["lse_c"], rep)
+        PU.compare("O_d", PU.to_f64(b.o_d), ref["o_d"], rep)
+        PU.compare_lse("LSE_d", PU.to_f64(b.lse_d), ref["lse_d"], rep)
+        for name, got, call, key in (("dQ_d", b.dq_d, "call2", "dq_d"), ("dK_d", b.dk_d, "call2", "dk_d"),
+                                     ("dV_d", b.dv_d, "call2", "dv_d"), ("dQ_c", b.dq_c, "call1", "dq_c"),
+                                     ("dK_c(2)", b.dk_c2, "call2", "dk_c"), ("dV_c(2)", b.dv_c2, "call2", "dv_c"),
+                                     ("dK_c(1)", b.dk_c1, "call1", "dk_c"), ("dV_c(1)", b.dv_c1, "call1", "dv_c")):
+            PU.compare_to_bound(name, PU.to_f64(got), ref[call][key], bnd[call][key], rep)
+    finally:
+        print("\n  " + "\n  ".join(rep), flush=True)
 
 
 def test_random_small_shapes():
@@ -251,6 +253,30 @@ def test_random_small_shapes():
         print("case random", i, dict(d=d, H=hk * g, Hk=hk, N=n, P=P, lens=lens, win=win, flags=flags), flush=True)
         shape = W.Shape("rnd%d" % i, n, P, 0, 0, hk * g, hk, d, win, seed=9000 + i)
         PU.full_parity(W.make_workload(shape, resp_lens=np.asarray(lens)), flags=flags, verbose=False)
+
+
+# The five shapes of wider one-off sweeps (590 shapes) that left the fixed element-wise allowance 2e-2 + 2^-8 |ref|
+# (by at most 1.6e-2).  Here they are held to the DERIVED bound instead -- the worst case of bf16 rounding of the
+# P / dS operands, of the stored O behind D, and of the outputs, summed over the terms of each element
+# (oracle/rounding_bound.py; reading G7/G8) -- with no fixed allowance at all: an error that bound cannot explain is
+# a defect, not rounding.  One-token prompts sum thousands of rows into one dK_c row; a two-key window makes dS
+# a difference of two nearly equal rounded values.
+OUT_OF_ALLOWANCE = [
+    # name, seed, N, P, lens, H, Hk, d, window, flags
+    ("p1_sum2808_d128", 9070, 5, 1, [33, 64, 33, 190, 31], 16, 2, 128, 257, 0),
+    ("p1_win64_d96", 9139, 2, 1, [63, 65], 9, 3, 96, 64, 0),
+    ("p1_accum_d512", 9156, 5, 1, [65, 31, 63, 1, 64], 12, 3, 512, 0, 1),
+    ("p64_d512", 9124, 2, 64, [65, 100], 2, 2, 512, 0, 0),
+    ("p1_win2_d96", 9038, 5, 1, [1, 32, 0, 33, 64], 9, 3, 96, 2, 0),
+]
+
+
+@pytest.mark.parametrize("case", OUT_OF_ALLOWANCE, ids=[c[0] for c in OUT_OF_ALLOWANCE])
+def test_shapes_beyond_the_fixed_allowance_meet_the_rounding_bound(case):
+    name, seed, N, P, lens, H, Hk, d, win, flags = case
+    print("case", name, flush=True)
+    shape = W.Shape(name, N, P, 0, 0, H, Hk, d, win, seed=seed)
+    PU.bounded_parity(W.make_workload(shape, resp_lens=np.asarray(lens)), flags=flags)
 
 
 def test_prompt_groups_in_one_graph():

@@ -346,18 +346,81 @@ def test_key_column_sampler_matches_dense_backward():
             np.testing.assert_allclose(x, y, rtol=1e-12, atol=1e-14)
 
 
-def test_row_samplers_give_dq():
+def test_row_samplers_give_o_lse_dq():
+    """response_row / prompt_row (one query row straight from Eq. 4 / Eq. 3) against the dense replicated pass:
+    O, LSE and dQ of every row and head of a small group, with and without a window."""
     rng = np.random.default_rng(14)
     H, Hk, d = 4, 2, 4
     g = _group(rng, 5, [4, 3], H, Hk, d)
+    P, cu = 5, g["cu"]
     for window in (0, 4):
-        full = orc.dualkv_backward(g["q_c"], g["k_c"], g["v_c"], g["q_d"], g["k_d"], g["v_d"], g["cu"], 0.6,
+        fwd = orc.dualkv_forward(g["q_c"], g["k_c"], g["v_c"], g["q_d"], g["k_d"], g["v_d"], cu, 0.6, window)
+        full = orc.dualkv_backward(g["q_c"], g["k_c"], g["v_c"], g["q_d"], g["k_d"], g["v_d"], cu, 0.6,
                                    g["do_c"], g["do_d"], window)
-        _, _, dq = orc.response_row(g["q_d"], g["k_c"], g["v_c"], g["k_d"], g["v_d"], g["cu"], 0.6, 1, 2, 3, window,
-                                    do_row=g["do_d"][g["cu"][1] + 2, 3])
-        np.testing.assert_allclose(dq, full["dq_d"][g["cu"][1] + 2, 3], rtol=1e-11, atol=1e-13)
-        _, _, dqc = orc.prompt_row(g["q_c"], g["k_c"], g["v_c"], 0.6, 3, 1, window, do_row=g["do_c"][3, 1])
-        np.testing.assert_allclose(dqc, full["dq_c"][3, 1], rtol=1e-11, atol=1e-13)
+        for i in range(2):
+            for r in range(int(cu[i + 1] - cu[i])):
+                for h in range(H):
+                    row = cu[i] + r
+                    o, lse, dq = orc.response_row(g["q_d"], g["k_c"], g["v_c"], g["k_d"], g["v_d"], cu, 0.6, i, r, h,
+                                                  window, do_row=g["do_d"][row, h])
+                    np.testing.assert_allclose(o, fwd["o_d"][row, h], rtol=1e-12, atol=1e-14)
+                    assert abs(lse - fwd["lse_d"][h, row]) < 1e-12
+                    np.testing.assert_allclose(dq, full["dq_d"][row, h], rtol=1e-11, atol=1e-13)
+        # prompt rows: the dense pass of the prompt alone (attn_fwd_seq is pinned by closed forms above) ...
+        o_c, lse_c = orc.attn_fwd_seq(g["q_c"], g["k_c"], g["v_c"], 0.6, window)
+        for t in range(P):
+            for h in range(H):
+                o, lse, dqc = orc.prompt_row(g["q_c"], g["k_c"], g["v_c"], 0.6, t, h, window, do_row=g["do_c"][t, h])
+                np.testing.assert_allclose(o, o_c[t, h], rtol=1e-12, atol=1e-14)
+                assert abs(lse - lse_c[h, t]) < 1e-12
+                # ... and the prompt rows of the replicated group pass (Sec. 2.2: identical in every replica)
+                np.testing.assert_allclose(o, fwd["o_c"][t, h], rtol=1e-12, atol=1e-14)
+                assert abs(lse - fwd["lse_c"][h, t]) < 1e-12
+                np.testing.assert_allclose(dqc, full["dq_c"][t, h], rtol=1e-11, atol=1e-13)
+    # closed form: zero keys -> LSE_t = log(t + 1) (window: log min(t + 1, W)), O_t = mean of the visible values
+    kz = np.zeros_like(g["k_c"])
+    for t in range(P):
+        o, lse, _ = orc.prompt_row(g["q_c"], kz, g["v_c"], 0.6, t, 3)
+        assert abs(lse - math.log(t + 1)) < 1e-13
+        np.testing.assert_allclose(o, g["v_c"][:t + 1, 1].mean(axis=0), rtol=1e-13)
+        o, lse, _ = orc.prompt_row(g["q_c"], kz, g["v_c"], 0.6, t, 0, window=2)
+        assert abs(lse - math.log(min(t + 1, 2))) < 1e-13
+        np.testing.assert_allclose(o, g["v_c"][max(0, t - 1):t + 1, 0].mean(axis=0), rtol=1e-13)
+
+
+def test_packings_hand_example():
+    """The two packings (Eq. 1 <-> Eq. 5) and their position ids (App. A.2) on a hand-written example:
+    P = 3 prompt records a b c, responses of 2, 0 and 1 records (u v | | w)."""
+    cu = np.array([0, 2, 2, 3])
+    x_c = np.array([[10], [11], [12]])            # a b c
+    x_d = np.array([[20], [21], [30]])            # u v w
+    rep, cu_rep = orc.replicated_layout(3, cu, x_c, x_d)
+    #           seq 0: a b c u v | seq 1: a b c | seq 2: a b c w
+    assert rep[:, 0].tolist() == [10, 11, 12, 20, 21, 10, 11, 12, 10, 11, 12, 30]
+    assert cu_rep.tolist() == [0, 5, 8, 12]
+    assert orc.position_ids_replicated(3, cu).tolist() == [0, 1, 2, 3, 4, 0, 1, 2, 0, 1, 2, 3]
+    # single-prompt packing: a b c | u v | | w, every response restarts at position P
+    assert orc.single_prompt_layout(3, cu, rep)[:, 0].tolist() == [10, 11, 12, 20, 21, 30]
+    assert orc.position_ids_single_prompt(3, cu).tolist() == [0, 1, 2, 3, 4, 3]
+    # no prompt: both packings coincide
+    rep0, cu0 = orc.replicated_layout(0, cu, x_c[:0], x_d)
+    assert rep0[:, 0].tolist() == [20, 21, 30] and cu0.tolist() == [0, 2, 2, 3]
+    assert orc.position_ids_replicated(0, cu).tolist() == [0, 1, 0] == orc.position_ids_single_prompt(0, cu).tolist()
+    # the position of a response row in the single-prompt packing is the one it has inside its replica
+    rng = np.random.default_rng(3)
+    for _ in range(10):
+        P = int(rng.integers(0, 6))
+        lens = rng.integers(0, 5, size=int(rng.integers(1, 5)))
+        cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+        pos_rep = orc.position_ids_replicated(P, cu)
+        tags_c = np.arange(P)[:, None]
+        tags_d = 1000 + np.arange(int(cu[-1]))[:, None]
+        rep, _ = orc.replicated_layout(P, cu, tags_c, tags_d)
+        pos_sp = orc.position_ids_single_prompt(P, cu)
+        sp = orc.single_prompt_layout(P, cu, rep)[:, 0]
+        assert sp.tolist() == list(range(P)) + [1000 + x for x in range(int(cu[-1]))]
+        for tag, pos in zip(sp, pos_sp):
+            assert set(pos_rep[rep[:, 0] == tag].tolist()) == {int(pos)}
 
 
 # ---------------------------------------------------------------- counting / analytic helpers
