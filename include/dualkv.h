@@ -54,6 +54,7 @@ extern "C" {
 #define DUALKV_E_WORKSPACE   (-3)  /* workspace pointer NULL or smaller than dualkv_workspace_bytes  */
 #define DUALKV_E_ALIGN       (-4)  /* pointer not 16-byte aligned or stride not a multiple of 8      */
 #define DUALKV_E_HIP         (-5)  /* a HIP runtime call (launch) failed                             */
+#define DUALKV_E_SCRATCH     (-6)  /* dualkv_bwd_noalloc: the shape needs more than DUALKV_STATIC_SCRATCH_BYTES */
 
 #define DUALKV_OP_CTX_FWD 0
 #define DUALKV_OP_CTX_BWD 1
@@ -140,6 +141,24 @@ int dualkv_bwd(const dualkv_shape* shape, dualkv_tin do_d, dualkv_tin o_d, const
                dualkv_tout dq_d, dualkv_tout dk_c, dualkv_tout dv_c, dualkv_tout dk_d, dualkv_tout dv_d,
                float* dk_c_acc32, float* dv_c_acc32,
                void* workspace, size_t workspace_bytes, void* stream);
+
+/* dualkv_bwd for callers that cannot allocate device memory and have no workspace to hand over: code under HIP
+ * graph capture, tight serving / training loops, harnesses that forbid hipMalloc.  Same arguments, results and
+ * error codes as dualkv_bwd, without the workspace pair: the scratch (D, LSE in base-2 units, and the fp32
+ * accumulators of the split shared-prompt path) lives in a static device array of DUALKV_STATIC_SCRATCH_BYTES inside
+ * the library, one per GPU the library is loaded on, held until the process ends.  The call allocates nothing and
+ * frees nothing; its first use on a device looks the array's address up (make that first call outside a capture).
+ * A shape whose dualkv_workspace_bytes(shape, DUALKV_OP_BWD) exceeds DUALKV_STATIC_SCRATCH_BYTES is rejected with
+ * DUALKV_E_SCRATCH before anything is launched.  Every call on a GPU uses that GPU's one array: what must start
+ * at zero is cleared by the call itself, but two calls that overlap in time on one GPU (different streams,
+ * different threads) race -- serialise them.  The DUALKV_FLAG_SKIP_* flags work as in dualkv_bwd, provided no other
+ * call used the scratch in between. */
+#define DUALKV_STATIC_SCRATCH_BYTES (32u << 20)
+int dualkv_bwd_noalloc(const dualkv_shape* shape, dualkv_tin do_d, dualkv_tin o_d, const float* lse_d,
+                       dualkv_tin q_d, dualkv_tin k_c, dualkv_tin v_c, dualkv_tin k_d, dualkv_tin v_d,
+                       const int32_t* cu_seqlens_dev, const int32_t* cu_seqlens_host,
+                       dualkv_tout dq_d, dualkv_tout dk_c, dualkv_tout dv_c, dualkv_tout dk_d, dualkv_tout dv_d,
+                       float* dk_c_acc32, float* dv_c_acc32, void* stream);
 
 /* fp32 -> bf16 cast of the accumulated shared-prompt gradients (Alg. 2), acc32: (P,H_k,d) contiguous. */
 int dualkv_finalize_ctx_grads(const dualkv_shape* shape, const float* dk_c_acc32, const float* dv_c_acc32,

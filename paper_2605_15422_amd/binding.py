@@ -23,7 +23,8 @@ if not os.path.exists(LIB_PATH):
 
 lib = C.CDLL(LIB_PATH)
 
-OK, E_INVALID, E_UNSUPPORTED, E_WORKSPACE, E_ALIGN, E_HIP = 0, -1, -2, -3, -4, -5
+OK, E_INVALID, E_UNSUPPORTED, E_WORKSPACE, E_ALIGN, E_HIP, E_SCRATCH = 0, -1, -2, -3, -4, -5, -6
+STATIC_SCRATCH_BYTES = 32 << 20
 OP_CTX_FWD, OP_CTX_BWD, OP_FWD, OP_BWD = 0, 1, 2, 3
 FLAG_ACCUM_CTX_F32 = 1
 FLAG_SKIP_DQ = 2
@@ -31,6 +32,7 @@ FLAG_SKIP_DKDV = 4
 FLAG_SKIP_PRE = 8
 
 EXPORTS = ["dualkv_workspace_bytes", "dualkv_ctx_fwd", "dualkv_ctx_bwd", "dualkv_fwd", "dualkv_bwd",
+           "dualkv_bwd_noalloc",
            "dualkv_finalize_ctx_grads", "dualkv_repack", "dualkv_replicate", "dualkv_label_map",
            "dualkv_strerror", "dualkv_version"]
 
@@ -63,6 +65,8 @@ lib.dualkv_fwd.argtypes = [_PS, TIn, TIn, TIn, TIn, TIn, C.c_void_p, C.c_void_p,
 lib.dualkv_bwd.argtypes = [_PS, TIn, TIn, C.c_void_p, TIn, TIn, TIn, TIn, TIn, C.c_void_p, C.c_void_p,
                            TOut, TOut, TOut, TOut, TOut, C.c_void_p, C.c_void_p,
                            C.c_void_p, C.c_size_t, C.c_void_p]
+lib.dualkv_bwd_noalloc.argtypes = [_PS, TIn, TIn, C.c_void_p, TIn, TIn, TIn, TIn, TIn, C.c_void_p, C.c_void_p,
+                                   TOut, TOut, TOut, TOut, TOut, C.c_void_p, C.c_void_p, C.c_void_p]
 lib.dualkv_finalize_ctx_grads.argtypes = [_PS, C.c_void_p, C.c_void_p, TOut, TOut, C.c_void_p]
 for _f in (lib.dualkv_repack, lib.dualkv_replicate):
     _f.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
@@ -177,6 +181,15 @@ def dualkv_bwd(shape, do_d, o_d, lse_d, q_d, k_c, v_c, k_d, v_d, cu_seqlens_dev,
                           _tin(k_d), _tin(v_d), _ptr(cu_seqlens_dev), h[0] if h else None,
                           _tout(dq_d), _tout(dk_c), _tout(dv_c), _tout(dk_d), _tout(dv_d),
                           _ptr(dk_c_acc32), _ptr(dv_c_acc32), wp, wb, _stream()), "dualkv_bwd")
+
+
+def dualkv_bwd_noalloc(shape, do_d, o_d, lse_d, q_d, k_c, v_c, k_d, v_d, cu_seqlens_dev, cu_seqlens_host,
+                       dq_d, dk_c, dv_c, dk_d, dv_d, dk_c_acc32=None, dv_c_acc32=None):
+    h = _host_i32(cu_seqlens_host)
+    _check(lib.dualkv_bwd_noalloc(C.byref(shape), _tin(do_d), _tin(o_d), _ptr(lse_d), _tin(q_d), _tin(k_c), _tin(v_c),
+                                  _tin(k_d), _tin(v_d), _ptr(cu_seqlens_dev), h[0] if h else None,
+                                  _tout(dq_d), _tout(dk_c), _tout(dv_c), _tout(dk_d), _tout(dv_d),
+                                  _ptr(dk_c_acc32), _ptr(dv_c_acc32), _stream()), "dualkv_bwd_noalloc")
 
 
 def dualkv_finalize_ctx_grads(shape, dk_c_acc32, dv_c_acc32, dk_c, dv_c):

@@ -1,10 +1,14 @@
 // C ABI of the library (include/dualkv.h): host-side validation, workspace carving and dispatch.
 // Nothing here touches device memory except through kernel launches on the caller's stream.
 #include <cstdlib>
+#include <mutex>
 #include "../../include/dualkv.h"
 
 #include "common.h"
 #include "launch.h"
+
+// Scratch of dualkv_bwd_noalloc (see static_scratch below).  Host code never passes this name to a kernel.
+static __device__ __align__(256) unsigned char scratch[DUALKV_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -122,11 +126,118 @@ void base_params(AttnParams& p, const dualkv_shape* s) {
   p.n_split = 1;
 }
 
+
+// ---- the Call-2 backward, shared by dualkv_bwd (caller's workspace) and dualkv_bwd_noalloc (static scratch)
+int bwd_impl(const dualkv_shape* shape, dualkv_tin do_d, dualkv_tin o_d, const float* lse_d, dualkv_tin q_d,
+               dualkv_tin k_c, dualkv_tin v_c, dualkv_tin k_d, dualkv_tin v_d, const int32_t* cu_seqlens_dev,
+               const int32_t* cu_seqlens_host, dualkv_tout dq_d, dualkv_tout dk_c, dualkv_tout dv_c, dualkv_tout dk_d,
+               dualkv_tout dv_d, float* dk_c_acc32, float* dv_c_acc32, void* workspace, size_t workspace_bytes,
+               void* stream) {
+  int rc = check_shape(shape, false);
+  if (rc != DUALKV_OK) return rc;
+  if ((rc = check_cu_host(shape, cu_seqlens_host))) return rc;
+  const int P = shape->ctx_len, T = shape->total_resp, d = shape->head_dim;
+  const bool accum = (shape->flags & DUALKV_FLAG_ACCUM_CTX_F32) != 0;
+  if (T > 0) {
+    if (cu_seqlens_dev == nullptr || lse_d == nullptr) return DUALKV_E_INVALID;
+    if ((rc = check_in(do_d, T, d)) || (rc = check_in(o_d, T, d)) || (rc = check_in(q_d, T, d)) ||
+        (rc = check_in(k_d, T, d)) || (rc = check_in(v_d, T, d)) || (rc = check_out(dq_d, T, d)) ||
+        (rc = check_out(dk_d, T, d)) || (rc = check_out(dv_d, T, d)))
+      return rc;
+  }
+  if ((rc = check_in(k_c, P, d)) || (rc = check_in(v_c, P, d))) return rc;
+  if (accum) {
+    if (P > 0 && (dk_c_acc32 == nullptr || dv_c_acc32 == nullptr)) return DUALKV_E_INVALID;
+    if ((reinterpret_cast<uintptr_t>(dk_c_acc32) | reinterpret_cast<uintptr_t>(dv_c_acc32)) % 16) return DUALKV_E_ALIGN;
+  } else if ((rc = check_out(dk_c, P, d)) || (rc = check_out(dv_c, P, d))) {
+    return rc;
+  }
+  const BwdWorkspace w = bwd_workspace(shape, false);
+  if (w.total > 0 && (workspace == nullptr || workspace_bytes < w.total)) return DUALKV_E_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(workspace) % 16) return DUALKV_E_ALIGN;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int64_t n_acc = (int64_t)P * shape->n_kv_heads * d;
+
+  AttnParams p;
+  base_params(p, shape);
+  p.q = view(q_d);
+  p.kc = view(k_c);
+  p.vc = view(v_c);
+  p.kd = view(k_d);
+  p.vd = view(v_d);
+  p.o = view(o_d);
+  p.dout = view(do_d);
+  p.dq = view(dq_d);
+  p.dkd = view(dk_d);
+  p.dvd = view(dv_d);
+  p.lse = const_cast<float*>(lse_d);
+  p.dvec = reinterpret_cast<float*>(static_cast<char*>(workspace) + w.dvec_off);
+  p.lse2 = reinterpret_cast<float*>(static_cast<char*>(workspace) + w.lse2_off);
+  p.cu = cu_seqlens_dev;
+  p.n_seqs = shape->n_seqs;
+  p.ctx_len = P;
+  p.total = T;
+  p.max_rows = shape->max_resp;
+
+  const bool scratch = !accum && w.acc_bytes > 0;
+  if (accum) {
+    p.dkc_acc = dk_c_acc32;
+    p.dvc_acc = dv_c_acc32;
+    p.n_split = ctx_split(shape);
+  } else if (scratch) {
+    p.dkc_acc = reinterpret_cast<float*>(static_cast<char*>(workspace) + w.acc_off);
+    p.dvc_acc = reinterpret_cast<float*>(static_cast<char*>(workspace) + w.acc_off + w.acc_bytes);
+    p.n_split = ctx_split(shape);
+    // zero-initialise the fp32 scratch (Alg. 1, "Require: zero-initialized")
+    if (!(shape->flags & DUALKV_FLAG_SKIP_DKDV)) {
+      if ((rc = hip_rc(dkv::launch_fill_f32(p.dkc_acc, n_acc, 0.f, st)))) return rc;
+      if ((rc = hip_rc(dkv::launch_fill_f32(p.dvc_acc, n_acc, 0.f, st)))) return rc;
+    }
+  } else {
+    p.dkc = view(dk_c);
+    p.dvc = view(dv_c);
+  }
+  const bool do_dq = !(shape->flags & DUALKV_FLAG_SKIP_DQ), do_dkdv = !(shape->flags & DUALKV_FLAG_SKIP_DKDV);
+  if (T > 0 && !(shape->flags & DUALKV_FLAG_SKIP_PRE) &&
+      (rc = hip_rc(dkv::launch_dot_do_o(p.dout, p.o, p.lse, p.dvec, p.lse2, T, p.H, d, st))))
+    return rc;
+  if (do_dkdv && (rc = hip_rc(run_dkdv(p, d, st)))) return rc;
+  if (scratch && do_dkdv) {
+    // Stage 2 (Alg. 2): cast the accumulated prompt gradients once
+    if ((rc = hip_rc(dkv::launch_convert_ctx(p.dkc_acc, view(dk_c), P, p.Hk, d, 1.0f, st)))) return rc;
+    if ((rc = hip_rc(dkv::launch_convert_ctx(p.dvc_acc, view(dv_c), P, p.Hk, d, 1.0f, st)))) return rc;
+  }
+  if (T > 0 && do_dq) return hip_rc(run_dq(p, d, st));
+  return DUALKV_OK;
+}
+
+
+// ---- static scratch of dualkv_bwd_noalloc: one array per GPU the library is loaded on, held until the process
+// ends.  The array's name is only a host-side handle: its device address is looked up once per device (with that
+// device current) and only that address is ever handed to kernels.
+constexpr size_t kStaticScratchBytes = DUALKV_STATIC_SCRATCH_BYTES;
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+int static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return DUALKV_E_HIP;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return DUALKV_E_HIP;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return DUALKV_OK;
+}
+
 }  // namespace
 
 extern "C" {
 
-int dualkv_version(void) { return 100; }
+int dualkv_version(void) { return 200; }
 
 const char* dualkv_strerror(int code) {
   switch (code) {
@@ -136,6 +247,7 @@ const char* dualkv_strerror(int code) {
     case DUALKV_E_WORKSPACE: return "workspace missing or too small";
     case DUALKV_E_ALIGN: return "pointer not 16-byte aligned or stride not a multiple of 8 elements";
     case DUALKV_E_HIP: return "HIP runtime error";
+    case DUALKV_E_SCRATCH: return "shape needs more than the library's static scratch (DUALKV_STATIC_SCRATCH_BYTES)";
   }
   return "unknown error";
 }
@@ -275,82 +387,21 @@ int dualkv_bwd(const dualkv_shape* shape, dualkv_tin do_d, dualkv_tin o_d, const
                const int32_t* cu_seqlens_host, dualkv_tout dq_d, dualkv_tout dk_c, dualkv_tout dv_c, dualkv_tout dk_d,
                dualkv_tout dv_d, float* dk_c_acc32, float* dv_c_acc32, void* workspace, size_t workspace_bytes,
                void* stream) {
+  return bwd_impl(shape, do_d, o_d, lse_d, q_d, k_c, v_c, k_d, v_d, cu_seqlens_dev, cu_seqlens_host, dq_d, dk_c, dv_c,
+                  dk_d, dv_d, dk_c_acc32, dv_c_acc32, workspace, workspace_bytes, stream);
+}
+
+int dualkv_bwd_noalloc(const dualkv_shape* shape, dualkv_tin do_d, dualkv_tin o_d, const float* lse_d, dualkv_tin q_d,
+                       dualkv_tin k_c, dualkv_tin v_c, dualkv_tin k_d, dualkv_tin v_d, const int32_t* cu_seqlens_dev,
+                       const int32_t* cu_seqlens_host, dualkv_tout dq_d, dualkv_tout dk_c, dualkv_tout dv_c,
+                       dualkv_tout dk_d, dualkv_tout dv_d, float* dk_c_acc32, float* dv_c_acc32, void* stream) {
   int rc = check_shape(shape, false);
   if (rc != DUALKV_OK) return rc;
-  if ((rc = check_cu_host(shape, cu_seqlens_host))) return rc;
-  const int P = shape->ctx_len, T = shape->total_resp, d = shape->head_dim;
-  const bool accum = (shape->flags & DUALKV_FLAG_ACCUM_CTX_F32) != 0;
-  if (T > 0) {
-    if (cu_seqlens_dev == nullptr || lse_d == nullptr) return DUALKV_E_INVALID;
-    if ((rc = check_in(do_d, T, d)) || (rc = check_in(o_d, T, d)) || (rc = check_in(q_d, T, d)) ||
-        (rc = check_in(k_d, T, d)) || (rc = check_in(v_d, T, d)) || (rc = check_out(dq_d, T, d)) ||
-        (rc = check_out(dk_d, T, d)) || (rc = check_out(dv_d, T, d)))
-      return rc;
-  }
-  if ((rc = check_in(k_c, P, d)) || (rc = check_in(v_c, P, d))) return rc;
-  if (accum) {
-    if (P > 0 && (dk_c_acc32 == nullptr || dv_c_acc32 == nullptr)) return DUALKV_E_INVALID;
-    if ((reinterpret_cast<uintptr_t>(dk_c_acc32) | reinterpret_cast<uintptr_t>(dv_c_acc32)) % 16) return DUALKV_E_ALIGN;
-  } else if ((rc = check_out(dk_c, P, d)) || (rc = check_out(dv_c, P, d))) {
-    return rc;
-  }
-  const BwdWorkspace w = bwd_workspace(shape, false);
-  if (w.total > 0 && (workspace == nullptr || workspace_bytes < w.total)) return DUALKV_E_WORKSPACE;
-  if (reinterpret_cast<uintptr_t>(workspace) % 16) return DUALKV_E_ALIGN;
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  const int64_t n_acc = (int64_t)P * shape->n_kv_heads * d;
-
-  AttnParams p;
-  base_params(p, shape);
-  p.q = view(q_d);
-  p.kc = view(k_c);
-  p.vc = view(v_c);
-  p.kd = view(k_d);
-  p.vd = view(v_d);
-  p.o = view(o_d);
-  p.dout = view(do_d);
-  p.dq = view(dq_d);
-  p.dkd = view(dk_d);
-  p.dvd = view(dv_d);
-  p.lse = const_cast<float*>(lse_d);
-  p.dvec = reinterpret_cast<float*>(static_cast<char*>(workspace) + w.dvec_off);
-  p.lse2 = reinterpret_cast<float*>(static_cast<char*>(workspace) + w.lse2_off);
-  p.cu = cu_seqlens_dev;
-  p.n_seqs = shape->n_seqs;
-  p.ctx_len = P;
-  p.total = T;
-  p.max_rows = shape->max_resp;
-
-  const bool scratch = !accum && w.acc_bytes > 0;
-  if (accum) {
-    p.dkc_acc = dk_c_acc32;
-    p.dvc_acc = dv_c_acc32;
-    p.n_split = ctx_split(shape);
-  } else if (scratch) {
-    p.dkc_acc = reinterpret_cast<float*>(static_cast<char*>(workspace) + w.acc_off);
-    p.dvc_acc = reinterpret_cast<float*>(static_cast<char*>(workspace) + w.acc_off + w.acc_bytes);
-    p.n_split = ctx_split(shape);
-    // zero-initialise the fp32 scratch (Alg. 1, "Require: zero-initialized")
-    if (!(shape->flags & DUALKV_FLAG_SKIP_DKDV)) {
-      if ((rc = hip_rc(dkv::launch_fill_f32(p.dkc_acc, n_acc, 0.f, st)))) return rc;
-      if ((rc = hip_rc(dkv::launch_fill_f32(p.dvc_acc, n_acc, 0.f, st)))) return rc;
-    }
-  } else {
-    p.dkc = view(dk_c);
-    p.dvc = view(dv_c);
-  }
-  const bool do_dq = !(shape->flags & DUALKV_FLAG_SKIP_DQ), do_dkdv = !(shape->flags & DUALKV_FLAG_SKIP_DKDV);
-  if (T > 0 && !(shape->flags & DUALKV_FLAG_SKIP_PRE) &&
-      (rc = hip_rc(dkv::launch_dot_do_o(p.dout, p.o, p.lse, p.dvec, p.lse2, T, p.H, d, st))))
-    return rc;
-  if (do_dkdv && (rc = hip_rc(run_dkdv(p, d, st)))) return rc;
-  if (scratch && do_dkdv) {
-    // Stage 2 (Alg. 2): cast the accumulated prompt gradients once
-    if ((rc = hip_rc(dkv::launch_convert_ctx(p.dkc_acc, view(dk_c), P, p.Hk, d, 1.0f, st)))) return rc;
-    if ((rc = hip_rc(dkv::launch_convert_ctx(p.dvc_acc, view(dv_c), P, p.Hk, d, 1.0f, st)))) return rc;
-  }
-  if (T > 0 && do_dq) return hip_rc(run_dq(p, d, st));
-  return DUALKV_OK;
+  if (bwd_workspace(shape, false).total > kStaticScratchBytes) return DUALKV_E_SCRATCH;
+  void* ws = nullptr;
+  if ((rc = static_scratch(&ws))) return rc;
+  return bwd_impl(shape, do_d, o_d, lse_d, q_d, k_c, v_c, k_d, v_d, cu_seqlens_dev, cu_seqlens_host, dq_d, dk_c, dv_c,
+                  dk_d, dv_d, dk_c_acc32, dv_c_acc32, ws, kStaticScratchBytes, stream);
 }
 
 int dualkv_finalize_ctx_grads(const dualkv_shape* shape, const float* dk_c_acc32, const float* dv_c_acc32,

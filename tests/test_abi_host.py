@@ -86,3 +86,11 @@ def test_argument_validation_before_launch():
     assert B.lib.dualkv_repack(1, 4, 4, None, 6, None, None, None, None) == B.E_ALIGN
     assert B.lib.dualkv_repack(0, 4, 4, None, 8, None, None, None, None) == B.E_INVALID
     assert "workspace" in B.dualkv_strerror(B.E_WORKSPACE)
+    # the allocation-free backward rejects shapes beyond its static scratch before it touches the device
+    big = B.make_shape(1, 0, 200000, 200000, 32, 8, 128)
+    assert B.dualkv_workspace_bytes(big, B.OP_BWD) > B.STATIC_SCRATCH_BYTES
+    rc = B.lib.dualkv_bwd_noalloc(C.byref(big), null, null, None, null, null, null, null, null, None, None,
+                                  nullo, nullo, nullo, nullo, nullo, None, None, None)
+    assert rc == B.E_SCRATCH and "static scratch" in B.dualkv_strerror(B.E_SCRATCH)
+    hdr = open(os.path.join(ROOT, "include", "dualkv.h")).read()
+    assert "#define DUALKV_STATIC_SCRATCH_BYTES (32u << 20)" in hdr and B.STATIC_SCRATCH_BYTES == 32 << 20
