@@ -1,10 +1,12 @@
 #!/usr/bin/env python3
 """Benchmark of the shared-prompt attention hot path on one MI355X.
 
-A step = one pass of the whole path over one synthetic group: Call 1 forward, Call 2 forward, Call 2
-backward (D preprocess, dK/dV, dQ), Call 1 backward.  Inputs are resident in HBM before timing starts.
-Prints ONE JSON line (metric, value = algorithmic TFLOP/s of the whole layer, ms_per_step = ms/layer, the
-roofline of the dominant kernel, the N-copy reference point and the CPU-oracle baseline).
+A step = one pass of the whole path over one synthetic group: Call 1 forward, Call 2 forward, clearing the fp32
+accumulators of the shared-prompt gradients, Call 2 backward (D preprocess, dK/dV, dQ), Call 1 backward, both adding
+their dK_c / dV_c terms into the fp32 accumulators, and the single cast of the Call-1 + Call-2 sum (Eq. 6, Alg. 2).
+Inputs are resident in HBM before timing starts.  Prints ONE JSON line (metric, value = algorithmic TFLOP/s of the
+whole layer, ms_per_step = ms/layer, the roofline of the dominant kernel, the other benchmark configs, the N-copy
+reference point and the CPU-oracle baseline).
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--config cfg2_qwen8b] [--no-ncopy] [--no-cpu]
 """
@@ -21,16 +23,22 @@ sys.path.insert(0, ROOT)
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per launch (read + written) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by the
-# calibration factors derived in profiles/cfg2_qwen8b_hbm_traffic.txt (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0).
-MEASURED_TRAFFIC_BYTES = {
-    ("cfg2_qwen8b", "fwd"): 2 * 230643 * 1024 + 133131 * 1024,
-    ("cfg2_qwen8b", "bwd_dq"): 2 * 297051 * 1024 + 131072 * 1024,
-    ("cfg2_qwen8b", "bwd_dkdv"): 2 * 785846 * 1024 + 99073 * 1024,
-    ("cfg2_qwen8b", "ctx_fwd"): 2 * 72123 * 1024 + 66563 * 1024,
-    ("cfg2_qwen8b", "ctx_bwd_dq"): 2 * 106473 * 1024 + 65536 * 1024,
-    ("cfg2_qwen8b", "ctx_bwd_dkdv"): 2 * 1578960 * 1024 + 32768 * 1024,
-}
+TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "hbm_traffic_table.txt")
+
+
+def measured_traffic(config, stage):
+    """HBM bytes per launch (read + written) of one stage's kernel, from the tracked table of rocprofv3 --pmc
+    FETCH_SIZE / WRITE_SIZE results (already scaled by the copy-kernel calibration stated in that file); None if the
+    table has no line for it."""
+    try:
+        with open(TRAFFIC_TABLE) as f:
+            for ln in f:
+                w = ln.split()
+                if len(w) >= 3 and not ln.startswith("#") and w[0] == config and w[1] == stage:
+                    return int(w[2])
+    except OSError:
+        pass
+    return None
 
 
 def _events(n):
@@ -38,17 +46,25 @@ def _events(n):
     return [torch.cuda.Event(enable_timing=True) for _ in range(n)]
 
 
+STAGES = ["ctx_fwd", "fwd", "zero_acc", "bwd_pre", "bwd_dkdv", "bwd_dq", "ctx_bwd_pre", "ctx_bwd_dkdv", "ctx_bwd_dq",
+          "finalize"]
+
+
 def time_layer(dg, bufs, steps, warmup):
-    """Times `steps` layer passes; returns (ms_per_step, per-stage average ms).
+    """Times `steps` layer passes; returns (ms_per_step, wall ms per step, per-stage average ms).
 
     The Call-2 / Call-1 backward is issued stage by stage (same kernels, same order as the plain call) so
-    that HIP events on the launch stream bracket every kernel of the path.
+    that HIP events on the launch stream bracket every kernel of the path.  With DUALKV_FLAG_ACCUM_CTX_F32 in the
+    group's flags (the default of this benchmark) both backward calls add into the fp32 accumulators, which are
+    cleared before and cast once after (Eq. 6); without it each call writes its own bf16 term and the two extra
+    stages are empty.
     """
     import torch
     from paper_2605_15422_amd import binding as B
 
     s = dg.shape_c
     base = s.flags
+    accum = bool(base & B.FLAG_ACCUM_CTX_F32)
 
     def shape_with(flags):
         c = type(s).from_buffer_copy(bytes(s))
@@ -58,15 +74,15 @@ def time_layer(dg, bufs, steps, warmup):
     s_pre = shape_with(B.FLAG_SKIP_DQ | B.FLAG_SKIP_DKDV)
     s_dkdv = shape_with(B.FLAG_SKIP_PRE | B.FLAG_SKIP_DQ)
     s_dq = shape_with(B.FLAG_SKIP_PRE | B.FLAG_SKIP_DKDV)
-    names = ["ctx_fwd", "fwd", "bwd_pre", "bwd_dkdv", "bwd_dq", "ctx_bwd_pre", "ctx_bwd_dkdv", "ctx_bwd_dq"]
+    dk2, dv2, dk1, dv1 = (None, None, None, None) if accum else (bufs.dk_c2, bufs.dv_c2, bufs.dk_c1, bufs.dv_c1)
 
     def bwd2(sh):
         B.dualkv_bwd(sh, dg.do_d, bufs.o_d, bufs.lse_d, dg.q_d, dg.k_c, dg.v_c, dg.k_d, dg.v_d, dg.cu_dev, None,
-                     bufs.dq_d, bufs.dk_c2, bufs.dv_c2, bufs.dk_d, bufs.dv_d, None, None, bufs.ws_bwd)
+                     bufs.dq_d, dk2, dv2, bufs.dk_d, bufs.dv_d, bufs.dk_c_acc, bufs.dv_c_acc, bufs.ws_bwd)
 
     def bwd1(sh):
-        B.dualkv_ctx_bwd(sh, dg.do_c, bufs.o_c, bufs.lse_c, dg.q_c, dg.k_c, dg.v_c, bufs.dq_c, bufs.dk_c1,
-                         bufs.dv_c1, None, None, bufs.ws_ctx_bwd)
+        B.dualkv_ctx_bwd(sh, dg.do_c, bufs.o_c, bufs.lse_c, dg.q_c, dg.k_c, dg.v_c, bufs.dq_c, dk1, dv1,
+                         bufs.dk_c_acc, bufs.dv_c_acc, bufs.ws_ctx_bwd)
 
     def one_step(ev):
         k = 0
@@ -76,6 +92,9 @@ def time_layer(dg, bufs, steps, warmup):
         ev[k].record(); k += 1
         B.dualkv_fwd(s, dg.q_d, dg.k_c, dg.v_c, dg.k_d, dg.v_d, dg.cu_dev, None, bufs.o_d, bufs.lse_d)
         ev[k].record(); k += 1
+        if accum:
+            B.dualkv_zero_ctx_grads(s, bufs.dk_c_acc, bufs.dv_c_acc)
+        ev[k].record(); k += 1
         for sh in (s_pre, s_dkdv, s_dq):
             bwd2(sh)
             ev[k].record(); k += 1
@@ -83,23 +102,72 @@ def time_layer(dg, bufs, steps, warmup):
             if s.ctx_len > 0:
                 bwd1(sh)
             ev[k].record(); k += 1
+        if accum:
+            B.dualkv_finalize_ctx_grads(s, bufs.dk_c_acc, bufs.dv_c_acc, bufs.dk_c, bufs.dv_c)
+        ev[k].record(); k += 1
 
-    dummy = _events(9)
+    nev = len(STAGES) + 1
+    dummy = _events(nev)
     for _ in range(warmup):
         one_step(dummy)
     torch.cuda.synchronize()
-    evs = [_events(9) for _ in range(steps)]
+    evs = [_events(nev) for _ in range(steps)]
     t0 = time.perf_counter()
     for i in range(steps):
         one_step(evs[i])
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
     gpu_ms = evs[0][0].elapsed_time(evs[-1][-1])
-    stage = {n: 0.0 for n in names}
+    stage = {n: 0.0 for n in STAGES}
     for ev in evs:
-        for j, n in enumerate(names):
+        for j, n in enumerate(STAGES):
             stage[n] += ev[j].elapsed_time(ev[j + 1]) / steps
     return max(gpu_ms, 0.0) / steps, wall_ms / steps, stage
+
+
+def random_device_group(shape, flags):
+    """A group of `shape` whose tensors are drawn on the device (torch.randn, seeded): for timing the other
+    configs without minutes of host-side number generation.  Lengths come from the same seeded recipe as the parity
+    workloads."""
+    import torch
+    from paper_2605_15422_amd import binding as B
+    from paper_2605_15422_amd import workloads as W
+    wl = W.make_workload(shape, tensors=False)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(shape.seed)
+    P, T, H, Hk, d = shape.ctx_len, wl.total_resp, shape.n_q_heads, shape.n_kv_heads, shape.head_dim
+
+    def rnd(rows, heads):
+        return torch.randn((rows, heads, d), generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+
+    shp = B.make_shape(shape.n_seqs, P, T, wl.max_resp, H, Hk, d, shape.window, wl.scale, flags)
+    dg = B.DeviceGroup(shp, rnd(P, H), rnd(P, Hk), rnd(P, Hk), rnd(T, H), rnd(T, Hk), rnd(T, Hk), rnd(P, H), rnd(T, H),
+                       torch.from_numpy(wl.cu_seqlens.copy()).cuda(), wl.cu_seqlens.copy())
+    return wl, dg
+
+
+def time_other_configs(names, flags, steps=2, warmup=1):
+    """ms/layer, algorithmic TFLOP/s and fraction of the MFMA peak of the other benchmark configs (same step)."""
+    import torch
+    from paper_2605_15422_amd import accounting as acc
+    from paper_2605_15422_amd import runner
+    from paper_2605_15422_amd import workloads as W
+    out = {}
+    for name in names:
+        shape = W.CONFIGS[name]
+        wl, dg = random_device_group(shape, flags)
+        bufs = runner.alloc(dg, poison=False)
+        n = 20 if name == "cfg1_tiny" else steps
+        ms, _, stage = time_layer(dg, bufs, n, warmup)
+        fl = acc.layer_flops(shape, wl.resp_lens)
+        tf = fl["layer"] / (ms * 1e-3) / 1e12
+        out[name] = {"ms_per_layer": round(ms, 4), "tflops": round(tf, 2), "frac_mfma_peak": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
+                     "layer_tflop": round(fl["layer"] / 1e12, 3), "steps": n,
+                     "fwd_ms": round(stage["ctx_fwd"] + stage["fwd"], 4),
+                     "bwd_ms": round(sum(v for k, v in stage.items() if k not in ("ctx_fwd", "fwd")), 4)}
+        del bufs, dg
+        torch.cuda.empty_cache()
+    return out
 
 
 def time_ncopy(wl, steps, warmup):
@@ -287,6 +355,10 @@ def main():
     ap.add_argument("--config", default="cfg2_qwen8b")
     ap.add_argument("--no-ncopy", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-others", action="store_true", help="skip the other benchmark configs")
+    ap.add_argument("--two-terms", action="store_true",
+                    help="time the mode that returns the Call-1 and Call-2 terms of dK_c / dV_c as two bf16 tensors "
+                         "(the paper's interface) instead of the fp32 joint accumulation with one cast")
     ap.add_argument("--ncopy-steps", type=int, default=2)
     ap.add_argument("--graph-groups", type=int, default=0,
                     help="also time this many prompt groups of the config, eagerly and as one captured graph")
@@ -305,11 +377,17 @@ def main():
     shape = W.CONFIGS[args.config]
     wl = W.make_workload(shape)
     fl = acc.layer_flops(shape, wl.resp_lens)
-    dg = B.upload(wl)
+    flags = 0 if args.two_terms else B.FLAG_ACCUM_CTX_F32
+    dg = B.upload(wl, flags)
     bufs = runner.alloc(dg, poison=False)
     torch.cuda.synchronize()
 
     ms, wall_ms, stage = time_layer(dg, bufs, args.steps, args.warmup)
+    # the other mode, for reference (fewer steps)
+    dg_alt = B.upload(wl, B.FLAG_ACCUM_CTX_F32 if args.two_terms else 0)
+    bufs_alt = runner.alloc(dg_alt, poison=False)
+    ms_alt, _, _ = time_layer(dg_alt, bufs_alt, max(3, args.steps // 3), 1)
+    del dg_alt, bufs_alt
 
     # dominant kernel and its roofline (MFMA bound: algorithmic flops of that kernel / its duration)
     d, H = shape.head_dim, shape.n_q_heads
@@ -325,7 +403,7 @@ def main():
                     "ctx_bwd_dkdv": "dkdv_kernel (Call 1)", "ctx_bwd_dq": "dq_kernel (Call 1)"}
     roofline = {"bound": "mfma", "kernel": kernel_names[dom], "achieved": round(achieved, 2),
                 "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
-                "traffic": MEASURED_TRAFFIC_BYTES.get((args.config, dom)), "kernel_ms": round(stage[dom], 4),
+                "traffic": measured_traffic(args.config, dom), "kernel_ms": round(stage[dom], 4),
                 "algorithmic_flops_per_launch": kern_flops[dom]}
 
     tflops = fl["layer"] / (ms * 1e-3) / 1e12
@@ -344,7 +422,10 @@ def main():
         "stage_ms": {k: round(v, 4) for k, v in stage.items()},
         "stage_tflops": {k: round(kern_flops[k] / (stage[k] * 1e-3) / 1e12, 1) for k in kern_flops if stage[k] > 0},
         "fwd_ms": round(stage["ctx_fwd"] + stage["fwd"], 4),
-        "bwd_ms": round(sum(stage[k] for k in stage if "bwd" in k), 4),
+        "bwd_ms": round(sum(v for k, v in stage.items() if k not in ("ctx_fwd", "fwd")), 4),
+        "ctx_grad_mode": ("two bf16 terms (Call 1, Call 2), summed by the caller" if args.two_terms else
+                          "fp32 joint accumulation of Call 1 + Call 2, one cast (Eq. 6 inside the timed step)"),
+        ("ms_per_step_joint_fp32" if args.two_terms else "ms_per_step_two_terms"): round(ms_alt, 4),
         "roofline": roofline,
         "ncopy_flop_ratio": round(fl["ncopy"] / fl["layer"], 3),   # FLOPs of N-copy attention over this layer's
     }
@@ -362,6 +443,10 @@ def main():
                         "what": "same kernels on the replicated N x (P+R_i) layout (ctx_len=0), fwd+bwd"}
     if not args.no_ncopy:
         out["layout_kernels"] = time_repack(wl)
+    if not args.no_others and args.config == "cfg2_qwen8b":
+        del dg
+        torch.cuda.empty_cache()
+        out["other_configs"] = time_other_configs(["cfg1_tiny", "cfg3_ragged", "cfg4_30b", "cfg5b_swa", "cfg5a_global"], flags)
     if args.graph_groups > 0:
         out["multi_group"] = time_groups(shape, args.graph_groups, max(args.steps, 20))
     if not args.no_cpu:

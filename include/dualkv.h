@@ -164,6 +164,10 @@ int dualkv_bwd_noalloc(const dualkv_shape* shape, dualkv_tin do_d, dualkv_tin o_
 int dualkv_finalize_ctx_grads(const dualkv_shape* shape, const float* dk_c_acc32, const float* dv_c_acc32,
                               dualkv_tout dk_c, dualkv_tout dv_c, void* stream);
 
+/* Clears the fp32 accumulators of DUALKV_FLAG_ACCUM_CTX_F32 mode ((P, H_k, d) contiguous each) with a fill kernel on
+ * `stream` (Alg. 1 "Require: zero-initialised accumulators"; no memset node, so it may be captured in a graph). */
+int dualkv_zero_ctx_grads(const dualkv_shape* shape, float* dk_c_acc32, float* dv_c_acc32, void* stream);
+
 /* Layout kernels (Eq. 1 <-> Eq. 5).  Rows are opaque records of row_bytes (multiple of 4) bytes.
  * Standard packing: sequence i occupies rows [i*P + cu[i], (i+1)*P + cu[i+1]) = prompt then response i.
  * Single-prompt packing: rows [0,P) prompt, row P + cu[i] + r = response i row r.

@@ -32,7 +32,7 @@ FLAG_SKIP_DKDV = 4
 FLAG_SKIP_PRE = 8
 
 EXPORTS = ["dualkv_workspace_bytes", "dualkv_ctx_fwd", "dualkv_ctx_bwd", "dualkv_fwd", "dualkv_bwd",
-           "dualkv_bwd_noalloc",
+           "dualkv_bwd_noalloc", "dualkv_zero_ctx_grads",
            "dualkv_finalize_ctx_grads", "dualkv_repack", "dualkv_replicate", "dualkv_label_map",
            "dualkv_strerror", "dualkv_version"]
 
@@ -67,6 +67,7 @@ lib.dualkv_bwd.argtypes = [_PS, TIn, TIn, C.c_void_p, TIn, TIn, TIn, TIn, TIn, C
                            C.c_void_p, C.c_size_t, C.c_void_p]
 lib.dualkv_bwd_noalloc.argtypes = [_PS, TIn, TIn, C.c_void_p, TIn, TIn, TIn, TIn, TIn, C.c_void_p, C.c_void_p,
                                    TOut, TOut, TOut, TOut, TOut, C.c_void_p, C.c_void_p, C.c_void_p]
+lib.dualkv_zero_ctx_grads.argtypes = [_PS, C.c_void_p, C.c_void_p, C.c_void_p]
 lib.dualkv_finalize_ctx_grads.argtypes = [_PS, C.c_void_p, C.c_void_p, TOut, TOut, C.c_void_p]
 for _f in (lib.dualkv_repack, lib.dualkv_replicate):
     _f.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
@@ -190,6 +191,11 @@ def dualkv_bwd_noalloc(shape, do_d, o_d, lse_d, q_d, k_c, v_c, k_d, v_d, cu_seql
                                   _tin(k_d), _tin(v_d), _ptr(cu_seqlens_dev), h[0] if h else None,
                                   _tout(dq_d), _tout(dk_c), _tout(dv_c), _tout(dk_d), _tout(dv_d),
                                   _ptr(dk_c_acc32), _ptr(dv_c_acc32), _stream()), "dualkv_bwd_noalloc")
+
+
+def dualkv_zero_ctx_grads(shape, dk_c_acc32, dv_c_acc32):
+    _check(lib.dualkv_zero_ctx_grads(C.byref(shape), _ptr(dk_c_acc32), _ptr(dv_c_acc32), _stream()),
+           "dualkv_zero_ctx_grads")
 
 
 def dualkv_finalize_ctx_grads(shape, dk_c_acc32, dv_c_acc32, dk_c, dv_c):

@@ -418,6 +418,18 @@ int dualkv_finalize_ctx_grads(const dualkv_shape* shape, const float* dk_c_acc32
   return hip_rc(dkv::launch_convert_ctx(dv_c_acc32, view(dv_c), P, shape->n_kv_heads, d, 1.0f, st));
 }
 
+int dualkv_zero_ctx_grads(const dualkv_shape* shape, float* dk_c_acc32, float* dv_c_acc32, void* stream) {
+  int rc = check_shape(shape, true);
+  if (rc != DUALKV_OK) return rc;
+  if (shape->ctx_len == 0) return DUALKV_OK;
+  if (dk_c_acc32 == nullptr || dv_c_acc32 == nullptr) return DUALKV_E_INVALID;
+  if ((reinterpret_cast<uintptr_t>(dk_c_acc32) | reinterpret_cast<uintptr_t>(dv_c_acc32)) % 16) return DUALKV_E_ALIGN;
+  const int64_t n = (int64_t)shape->ctx_len * shape->n_kv_heads * shape->head_dim;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if ((rc = hip_rc(dkv::launch_fill_f32(dk_c_acc32, n, 0.f, st)))) return rc;
+  return hip_rc(dkv::launch_fill_f32(dv_c_acc32, n, 0.f, st));
+}
+
 static int rows_copy_common(bool to_packed, int32_t n_seqs, int32_t ctx_len, int32_t total_resp,
                             const int32_t* cu, int64_t row_bytes, const void* src, void* dst, int32_t* pos,
                             void* stream) {

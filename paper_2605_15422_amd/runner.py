@@ -98,6 +98,5 @@ def layer_step(dg: B.DeviceGroup, b: LayerBuffers) -> None:
     """One pass of the whole hot path: both forward calls, then both backward calls."""
     forward(dg, b)
     if b.dk_c_acc is not None:
-        b.dk_c_acc.zero_()
-        b.dv_c_acc.zero_()
+        B.dualkv_zero_ctx_grads(dg.shape_c, b.dk_c_acc, b.dv_c_acc)
     backward(dg, b)

@@ -3,9 +3,15 @@
 The dense fp64 oracle is too slow at these sizes, so each config is checked three ways:
   1. seeded samples of query rows (O, LSE, dQ of both calls) against the oracle's one-row evaluation of
      Eq. 3 / Eq. 4, including first / last rows and rows next to tile edges;
-  2. a second backward with an upstream gradient that is non-zero only on a seeded set of rows: dK / dV of
-     sampled prompt keys and response keys of one KV head then depend on those rows only, and are compared
-     with the oracle's column evaluation (all sequences contribute to the shared prompt keys);
+  2. the shared accumulation itself (Sec. 3.2, Alg. 1 + Alg. 2, App. A.5), configs 2 and 3: with the DENSE upstream
+     gradient, dK_c / dV_c of a seeded sample of >= 256 prompt keys of one seeded KV head -- each the fp32 sum of
+     the contributions of every response row of all N sequences and the G heads of the group -- and dK_d / dV_d of
+     sampled response keys, element by element against the oracle's column evaluation over ALL rows of that head
+     group (one fp64 pass over its (row, key) pairs);
+     configs 4 and 5, where that pass takes many minutes: a second backward with an upstream gradient that is
+     non-zero only on a seeded set of rows: dK / dV of sampled prompt keys and response keys of one KV head then
+     depend on those rows only, and are compared with the oracle's column evaluation (all sequences contribute
+     to the shared prompt keys);
   3. identities that hold for the full dense-gradient outputs at any size: sum_j dV_j = sum_rows dO
      (softmax rows sum to one), sum_j dK_j = 0 (rows of dS sum to zero), <q,dq> = <k,dk> (scale symmetry),
      per KV head, over prompt + response keys of Call 2 and over the prompt keys of Call 1.
@@ -23,6 +29,9 @@ pytestmark = pytest.mark.gpu
 N_ROW_SAMPLES = 48
 N_SPARSE_ROWS = 24
 N_KEY_SAMPLES = 40
+N_DENSE_CTX_KEYS = 256          # prompt keys checked against the dense-gradient column evaluation (configs 2, 3)
+N_DENSE_DEC_KEYS = 64
+DENSE_COLUMN_CONFIGS = ("cfg2_qwen8b", "cfg3_ragged")
 
 
 def _say(*a):
@@ -50,7 +59,10 @@ def _sample_rows(rng, wl, n):
     return sorted(out)[:max(n, 1)] if len(out) > n else sorted(out)
 
 
-@pytest.mark.parametrize("name", ["cfg2_qwen8b", "cfg3_ragged", "cfg4_30b", "cfg5b_swa", "cfg5a_global"])
+# the five benchmark configs, plus two shapes of the paper-shape sweeps: a Tab. 1 point with N = 28 sequences and the
+# longest prompt of the prompt-length grid (P = 131072, where 32-bit offset arithmetic is most at risk)
+@pytest.mark.parametrize("name", ["cfg2_qwen8b", "cfg3_ragged", "cfg4_30b", "cfg5b_swa", "cfg5a_global",
+                                  "tab1_n28_p16k", "grid_p131072_mb4"])
 def test_full_size(name):
     import torch
     from paper_2605_15422_amd import binding as B, runner
@@ -134,7 +146,34 @@ def test_full_size(name):
             # every term is a bf16 value (2^-9 relative rounding, unbiased) -> the sums agree far inside 1e-2
             assert e_dv < 1e-2 and e_dk < 1e-2 and e_sym < 1e-2 and e_dv1 < 1e-2 and e_dk1 < 1e-2, rep[-1]
 
-        # ---- 2. sparse upstream gradient -> key columns of one KV head
+        # ---- 2a. dense upstream gradient: the N x G x R_i-way fp32 sum into each shared prompt key
+        if name in DENSE_COLUMN_CONFIGS:
+            _say("  dense-gradient key columns (all %d response rows x %d heads of KV head %d)" % (T, G, kv))
+            edge = [0, 1, 31, 32, 63, 64, 127, 128, 129, P // 2, P - 129, P - 128, P - 2, P - 1]
+            ctx_keys = sorted(set(edge + [int(x) for x in rng.choice(P, size=N_DENSE_CTX_KEYS, replace=False)]))
+            dec_keys = set()
+            for i in sorted(set([0, shape.n_seqs - 1, int(np.argmax(wl.resp_lens)), int(np.argmin(wl.resp_lens))])):
+                R = int(wl.resp_lens[i])
+                for j in (0, 1, 31, 32, 127, 128, R // 2, R - 2, R - 1):
+                    if 0 <= j < R:
+                        dec_keys.add((i, int(j)))
+            while len(dec_keys) < N_DENSE_DEC_KEYS:
+                i = int(rng.integers(0, shape.n_seqs))
+                if wl.resp_lens[i] > 0:
+                    dec_keys.add((i, int(rng.integers(0, wl.resp_lens[i]))))
+            dec_keys = sorted(dec_keys)
+            dk_c, dv_c, dk_dd, dv_dd = orc.key_columns_call2(
+                q_d, k_c, v_c, k_d, v_d, cu, wl.scale, do_d, 0, ctx_keys, dec_keys, Wn,
+                progress=lambda i: _say("    sequence %d / %d" % (i + 1, shape.n_seqs)) if i % 8 == 7 else None)
+            rep.append("dense dO: %d prompt keys and %d response keys of KV head %d, every one of the %d x %d "
+                       "(row, head) contributions summed" % (len(ctx_keys), len(dec_keys), kv, T, G))
+            PU.compare("dK_c(2)*", PU.to_f64(bufs.dk_c2[ctx_keys, kv]), dk_c, rep)
+            PU.compare("dV_c(2)*", PU.to_f64(bufs.dv_c2[ctx_keys, kv]), dv_c, rep)
+            didx = [int(cu[i]) + j for (i, j) in dec_keys]
+            PU.compare("dK_d*", PU.to_f64(bufs.dk_d[didx, kv]), dk_dd, rep)
+            PU.compare("dV_d*", PU.to_f64(bufs.dv_d[didx, kv]), dv_dd, rep)
+
+        # ---- 2b. sparse upstream gradient -> key columns of one KV head
         _say("  sparse-gradient backward")
         srows = _sample_rows(rng, wl, N_SPARSE_ROWS)
         do_sp = torch.zeros_like(dg.do_d)
