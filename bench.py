@@ -293,6 +293,56 @@ def time_repack(wl, reps=5):
     return res
 
 
+def groups_one_call(shape, dgs):
+    """Packs the groups (device copies) into the multi-group layout and returns a function that runs one layer pass
+    over all of them through the *_groups entry points."""
+    import numpy as np
+    import torch
+    from paper_2605_15422_amd import binding as B
+    cat = lambda name: torch.cat([getattr(dg, name) for dg in dgs], dim=0)
+    t = {n: cat(n) for n in ("q_c", "k_c", "v_c", "do_c", "q_d", "k_d", "v_d", "do_d")}
+    table, cu = [], [0]
+    c_off = seq = 0
+    for dg in dgs:
+        n, P = dg.shape_c.n_seqs, dg.shape_c.ctx_len
+        table.append((c_off, P, seq, seq + n))
+        c_off += P
+        seq += n
+        cu.extend(int(cu[-1] + x) for x in np.diff(dg.cu_host))
+    table = np.asarray(table, dtype=np.int32)
+    cu = np.asarray(cu, dtype=np.int32)
+    total_ctx, T = c_off, int(cu[-1])
+    H, Hk, d = shape.n_q_heads, shape.n_kv_heads, shape.head_dim
+    flags = B.FLAG_ACCUM_CTX_F32
+    shp = B.make_shape(seq, max(dg.shape_c.ctx_len for dg in dgs), T, int(np.diff(cu).max()), H, Hk, d, shape.window,
+                       0.0, flags)
+    shp_all = B.make_shape(1, total_ctx, 0, 0, H, Hk, d, shape.window, 0.0, flags)
+    g_dev, cu_dev = torch.from_numpy(table).cuda(), torch.from_numpy(cu).cuda()
+    ws = {op: torch.empty(max(16, B.dualkv_groups_workspace_bytes(shp, len(dgs), total_ctx, op)), dtype=torch.uint8,
+                          device="cuda") for op in (B.OP_CTX_FWD, B.OP_FWD, B.OP_CTX_BWD, B.OP_BWD)}
+    o_c, o_d = torch.empty_like(t["q_c"]), torch.empty_like(t["q_d"])
+    dq_c, dq_d = torch.empty_like(t["q_c"]), torch.empty_like(t["q_d"])
+    dk_d, dv_d = torch.empty_like(t["k_d"]), torch.empty_like(t["v_d"])
+    dk_c, dv_c = torch.empty_like(t["k_c"]), torch.empty_like(t["v_c"])
+    a_k = torch.empty(t["k_c"].shape, dtype=torch.float32, device="cuda")
+    a_v = torch.empty(t["v_c"].shape, dtype=torch.float32, device="cuda")
+    lse_c = torch.empty((H, total_ctx), dtype=torch.float32, device="cuda")
+    lse_d = torch.empty((H, T), dtype=torch.float32, device="cuda")
+
+    def run():
+        B.dualkv_ctx_fwd_groups(shp, g_dev, None, total_ctx, t["q_c"], t["k_c"], t["v_c"], o_c, lse_c, ws[B.OP_CTX_FWD])
+        B.dualkv_fwd_groups(shp, g_dev, None, total_ctx, t["q_d"], t["k_c"], t["v_c"], t["k_d"], t["v_d"], cu_dev, None,
+                            o_d, lse_d, ws[B.OP_FWD])
+        B.dualkv_zero_ctx_grads(shp_all, a_k, a_v)
+        B.dualkv_bwd_groups(shp, g_dev, None, total_ctx, t["do_d"], o_d, lse_d, t["q_d"], t["k_c"], t["v_c"], t["k_d"],
+                            t["v_d"], cu_dev, None, dq_d, None, None, dk_d, dv_d, a_k, a_v, ws[B.OP_BWD])
+        B.dualkv_ctx_bwd_groups(shp, g_dev, None, total_ctx, t["do_c"], o_c, lse_c, t["q_c"], t["k_c"], t["v_c"], dq_c,
+                                None, None, a_k, a_v, ws[B.OP_CTX_BWD])
+        B.dualkv_finalize_ctx_grads(shp_all, a_k, a_v, dk_c, dv_c)
+
+    return run
+
+
 def time_groups(shape, n_groups, steps):
     """`n_groups` prompt groups of `shape` (different seeds), one layer pass each: the per-group calls issued
     eagerly, and the same calls captured once in a HIP graph and replayed (one launch for all groups)."""
@@ -303,7 +353,7 @@ def time_groups(shape, n_groups, steps):
     for g in range(n_groups):
         sh = W.Shape("%s_g%d" % (shape.name, g), shape.n_seqs, shape.ctx_len, shape.resp_lo, shape.resp_hi,
                      shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.window, shape.seed + 100 * (g + 1))
-        dg = B.upload(W.make_workload(sh))
+        dg = B.upload(W.make_workload(sh), B.FLAG_ACCUM_CTX_F32)
         groups.append((dg, runner.alloc(dg, poison=False)))
 
     def all_groups():
@@ -331,9 +381,16 @@ def time_groups(shape, n_groups, steps):
         all_groups()
     with torch.cuda.graph(graph_forked):
         all_groups_forked()
+    one_call = groups_one_call(shape, [dg for dg, _ in groups])
+    one_call()
+    torch.cuda.synchronize()
+    graph_one = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph_one):
+        one_call()
     res = {}
     for name, fn in (("eager", all_groups), ("eager_streams", all_groups_forked), ("graph", graph.replay),
-                     ("graph_branches", graph_forked.replay)):
+                     ("graph_branches", graph_forked.replay), ("one_call", one_call),
+                     ("one_call_graph", graph_one.replay)):
         fn()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -343,7 +400,8 @@ def time_groups(shape, n_groups, steps):
         res[name] = round((time.perf_counter() - t0) * 1e3 / steps, 4)
     return {"groups": n_groups, **{k + "_ms": v for k, v in res.items()},
             "what": "wall time per pass over all groups: per-group calls issued one by one on one stream / on %d "
-                    "streams, and one replay of a HIP graph that captured them as a chain / as %d branches"
+                    "streams, one replay of a HIP graph that captured them as a chain / as %d branches, and the "
+                    "*_groups entry points (every kernel launched once for all groups), eagerly / as a graph"
                     % (len(side), len(side))}
 
 

@@ -26,8 +26,8 @@
  *     synchronises: all work is enqueued on `stream` (a hipStream_t passed as
  *     void*; NULL is the default stream).  The enqueued work consists of kernel
  *     launches only (no memset or copy nodes), so the calls may be issued on a
- *     stream under capture: several prompt groups (Sec. 2.2) are one call
- *     sequence each, captured once in a HIP graph and replayed with one launch.
+ *     stream under capture.  Several prompt groups (Sec. 2.2) are either one call of
+ *     the *_groups entry points, or one call sequence per group captured in a HIP graph.
  *   - Outputs are fully overwritten.  The only exception are the fp32
  *     accumulators in DUALKV_FLAG_ACCUM_CTX_F32 mode, which are added into.
  *   - Every entry point returns DUALKV_OK or a negative error code; arguments are
@@ -163,6 +163,55 @@ int dualkv_bwd_noalloc(const dualkv_shape* shape, dualkv_tin do_d, dualkv_tin o_
 /* fp32 -> bf16 cast of the accumulated shared-prompt gradients (Alg. 2), acc32: (P,H_k,d) contiguous. */
 int dualkv_finalize_ctx_grads(const dualkv_shape* shape, const float* dk_c_acc32, const float* dv_c_acc32,
                               dualkv_tout dk_c, dualkv_tout dv_c, void* stream);
+
+/* ---- Several prompt groups in one call (Sec. 2.2: a micro-batch holds the response groups of several prompts) ----
+ *
+ * All groups share H, H_k, head_dim, window and scale.  Packing: the prompts of the groups back to back in one set of
+ * prompt tensors (q_c, k_c, v_c, ...: total_ctx = sum_g P_g rows), the responses of all groups back to back in one set
+ * of response tensors with ONE cu_seqlens over all n_seqs sequences (sequences of group 0 first, then group 1, ...).
+ * A group is {first prompt row, P_g, first sequence, end sequence}; P_g = 0 and groups without sequences are allowed.
+ * In `shape`: n_seqs = all sequences, total_resp / max_resp over all of them, ctx_len = the LARGEST P_g (an upper bound
+ * is enough; it sizes the launch).  groups_dev: device array of n_groups entries, 16-byte aligned; groups_host
+ * (optional, may be NULL): host copy, used only to validate (sequence ranges partition [0, n_seqs) in order, prompts
+ * inside [0, total_ctx) and, for the ctx calls, packed back to back in group order).  Layouts of the other arguments
+ * as in the single-group calls with P replaced by total_ctx: lse_c is (H, total_ctx), dk_c / dv_c and the fp32
+ * accumulators are (total_ctx, H_k, d).  Each call runs the kernels of its single-group counterpart once for all
+ * groups (plus one tiny index kernel), instead of once per group.  Workspace: dualkv_groups_workspace_bytes (the forward calls need a small one too).
+ * dualkv_zero_ctx_grads / dualkv_finalize_ctx_grads serve the accumulators of all groups when given a shape whose
+ * ctx_len is total_ctx. */
+typedef struct dualkv_group {
+  int32_t ctx_offset;   /* first row of the group's prompt in the prompt tensors            */
+  int32_t ctx_len;      /* P_g >= 0                                                          */
+  int32_t seq_begin;    /* the group's sequences are [seq_begin, seq_end) of cu_seqlens      */
+  int32_t seq_end;
+} dualkv_group;
+
+int dualkv_groups_workspace_bytes(const dualkv_shape* shape, int32_t n_groups, int32_t total_ctx, int op,
+                                  size_t* out_bytes);
+int dualkv_ctx_fwd_groups(const dualkv_shape* shape, int32_t n_groups, const dualkv_group* groups_dev,
+                          const dualkv_group* groups_host, int32_t total_ctx,
+                          dualkv_tin q_c, dualkv_tin k_c, dualkv_tin v_c, dualkv_tout o_c, float* lse_c,
+                          void* workspace, size_t workspace_bytes, void* stream);
+int dualkv_fwd_groups(const dualkv_shape* shape, int32_t n_groups, const dualkv_group* groups_dev,
+                      const dualkv_group* groups_host, int32_t total_ctx,
+                      dualkv_tin q_d, dualkv_tin k_c, dualkv_tin v_c, dualkv_tin k_d, dualkv_tin v_d,
+                      const int32_t* cu_seqlens_dev, const int32_t* cu_seqlens_host,
+                      dualkv_tout o_d, float* lse_d, void* workspace, size_t workspace_bytes, void* stream);
+int dualkv_ctx_bwd_groups(const dualkv_shape* shape, int32_t n_groups, const dualkv_group* groups_dev,
+                          const dualkv_group* groups_host, int32_t total_ctx,
+                          dualkv_tin do_c, dualkv_tin o_c, const float* lse_c,
+                          dualkv_tin q_c, dualkv_tin k_c, dualkv_tin v_c,
+                          dualkv_tout dq_c, dualkv_tout dk_c, dualkv_tout dv_c,
+                          float* dk_c_acc32, float* dv_c_acc32,
+                          void* workspace, size_t workspace_bytes, void* stream);
+int dualkv_bwd_groups(const dualkv_shape* shape, int32_t n_groups, const dualkv_group* groups_dev,
+                      const dualkv_group* groups_host, int32_t total_ctx,
+                      dualkv_tin do_d, dualkv_tin o_d, const float* lse_d,
+                      dualkv_tin q_d, dualkv_tin k_c, dualkv_tin v_c, dualkv_tin k_d, dualkv_tin v_d,
+                      const int32_t* cu_seqlens_dev, const int32_t* cu_seqlens_host,
+                      dualkv_tout dq_d, dualkv_tout dk_c, dualkv_tout dv_c, dualkv_tout dk_d, dualkv_tout dv_d,
+                      float* dk_c_acc32, float* dv_c_acc32,
+                      void* workspace, size_t workspace_bytes, void* stream);
 
 /* Clears the fp32 accumulators of DUALKV_FLAG_ACCUM_CTX_F32 mode ((P, H_k, d) contiguous each) with a fill kernel on
  * `stream` (Alg. 1 "Require: zero-initialised accumulators"; no memset node, so it may be captured in a graph). */

@@ -32,7 +32,8 @@ FLAG_SKIP_DKDV = 4
 FLAG_SKIP_PRE = 8
 
 EXPORTS = ["dualkv_workspace_bytes", "dualkv_ctx_fwd", "dualkv_ctx_bwd", "dualkv_fwd", "dualkv_bwd",
-           "dualkv_bwd_noalloc", "dualkv_zero_ctx_grads",
+           "dualkv_bwd_noalloc", "dualkv_zero_ctx_grads", "dualkv_groups_workspace_bytes", "dualkv_ctx_fwd_groups",
+           "dualkv_fwd_groups", "dualkv_ctx_bwd_groups", "dualkv_bwd_groups",
            "dualkv_finalize_ctx_grads", "dualkv_repack", "dualkv_replicate", "dualkv_label_map",
            "dualkv_strerror", "dualkv_version"]
 
@@ -52,6 +53,10 @@ class TOut(C.Structure):
     _fields_ = [("ptr", C.c_void_p), ("tok_stride", C.c_int64), ("head_stride", C.c_int64)]
 
 
+class Group(C.Structure):
+    _fields_ = [("ctx_offset", C.c_int32), ("ctx_len", C.c_int32), ("seq_begin", C.c_int32), ("seq_end", C.c_int32)]
+
+
 _PS = C.POINTER(Shape)
 lib.dualkv_version.restype = C.c_int
 lib.dualkv_strerror.restype = C.c_char_p
@@ -67,6 +72,12 @@ lib.dualkv_bwd.argtypes = [_PS, TIn, TIn, C.c_void_p, TIn, TIn, TIn, TIn, TIn, C
                            C.c_void_p, C.c_size_t, C.c_void_p]
 lib.dualkv_bwd_noalloc.argtypes = [_PS, TIn, TIn, C.c_void_p, TIn, TIn, TIn, TIn, TIn, C.c_void_p, C.c_void_p,
                                    TOut, TOut, TOut, TOut, TOut, C.c_void_p, C.c_void_p, C.c_void_p]
+_GRP = [_PS, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32]
+lib.dualkv_groups_workspace_bytes.argtypes = [_PS, C.c_int32, C.c_int32, C.c_int, C.POINTER(C.c_size_t)]
+lib.dualkv_ctx_fwd_groups.argtypes = _GRP + lib.dualkv_ctx_fwd.argtypes[1:]
+lib.dualkv_fwd_groups.argtypes = _GRP + lib.dualkv_fwd.argtypes[1:]
+lib.dualkv_ctx_bwd_groups.argtypes = _GRP + lib.dualkv_ctx_bwd.argtypes[1:]
+lib.dualkv_bwd_groups.argtypes = _GRP + lib.dualkv_bwd.argtypes[1:]
 lib.dualkv_zero_ctx_grads.argtypes = [_PS, C.c_void_p, C.c_void_p, C.c_void_p]
 lib.dualkv_finalize_ctx_grads.argtypes = [_PS, C.c_void_p, C.c_void_p, TOut, TOut, C.c_void_p]
 for _f in (lib.dualkv_repack, lib.dualkv_replicate):
@@ -191,6 +202,62 @@ def dualkv_bwd_noalloc(shape, do_d, o_d, lse_d, q_d, k_c, v_c, k_d, v_d, cu_seql
                                   _tin(k_d), _tin(v_d), _ptr(cu_seqlens_dev), h[0] if h else None,
                                   _tout(dq_d), _tout(dk_c), _tout(dv_c), _tout(dk_d), _tout(dv_d),
                                   _ptr(dk_c_acc32), _ptr(dv_c_acc32), _stream()), "dualkv_bwd_noalloc")
+
+
+def _grp(groups_dev, groups_host):
+    """(device int32 tensor (n, 4), optional host int32 array (n, 4)) -> the four leading group arguments."""
+    import numpy as np
+    n = int(groups_dev.shape[0])
+    h = None
+    if groups_host is not None:
+        h = np.ascontiguousarray(groups_host, dtype=np.int32)
+        assert h.shape == (n, 4)
+    return n, _ptr(groups_dev), (h.ctypes.data_as(C.c_void_p) if h is not None else None), h
+
+
+def dualkv_groups_workspace_bytes(shape: Shape, n_groups: int, total_ctx: int, op: int) -> int:
+    out = C.c_size_t(0)
+    _check(lib.dualkv_groups_workspace_bytes(C.byref(shape), n_groups, total_ctx, op, C.byref(out)),
+           "dualkv_groups_workspace_bytes")
+    return out.value
+
+
+def dualkv_ctx_fwd_groups(shape, groups_dev, groups_host, total_ctx, q_c, k_c, v_c, o_c, lse_c, workspace=None):
+    wp, wb = _ws(workspace)
+    n, gd, gh, _keep = _grp(groups_dev, groups_host)
+    _check(lib.dualkv_ctx_fwd_groups(C.byref(shape), n, gd, gh, total_ctx, _tin(q_c), _tin(k_c), _tin(v_c), _tout(o_c),
+                                     _ptr(lse_c), wp, wb, _stream()), "dualkv_ctx_fwd_groups")
+
+
+def dualkv_fwd_groups(shape, groups_dev, groups_host, total_ctx, q_d, k_c, v_c, k_d, v_d, cu_seqlens_dev,
+                      cu_seqlens_host, o_d, lse_d, workspace=None):
+    wp, wb = _ws(workspace)
+    h = _host_i32(cu_seqlens_host)
+    n, gd, gh, _keep = _grp(groups_dev, groups_host)
+    _check(lib.dualkv_fwd_groups(C.byref(shape), n, gd, gh, total_ctx, _tin(q_d), _tin(k_c), _tin(v_c), _tin(k_d),
+                                 _tin(v_d), _ptr(cu_seqlens_dev), h[0] if h else None, _tout(o_d), _ptr(lse_d), wp, wb,
+                                 _stream()), "dualkv_fwd_groups")
+
+
+def dualkv_ctx_bwd_groups(shape, groups_dev, groups_host, total_ctx, do_c, o_c, lse_c, q_c, k_c, v_c, dq_c, dk_c, dv_c,
+                          dk_c_acc32=None, dv_c_acc32=None, workspace=None):
+    wp, wb = _ws(workspace)
+    n, gd, gh, _keep = _grp(groups_dev, groups_host)
+    _check(lib.dualkv_ctx_bwd_groups(C.byref(shape), n, gd, gh, total_ctx, _tin(do_c), _tin(o_c), _ptr(lse_c),
+                                     _tin(q_c), _tin(k_c), _tin(v_c), _tout(dq_c), _tout(dk_c), _tout(dv_c),
+                                     _ptr(dk_c_acc32), _ptr(dv_c_acc32), wp, wb, _stream()), "dualkv_ctx_bwd_groups")
+
+
+def dualkv_bwd_groups(shape, groups_dev, groups_host, total_ctx, do_d, o_d, lse_d, q_d, k_c, v_c, k_d, v_d,
+                      cu_seqlens_dev, cu_seqlens_host, dq_d, dk_c, dv_c, dk_d, dv_d, dk_c_acc32=None, dv_c_acc32=None,
+                      workspace=None):
+    wp, wb = _ws(workspace)
+    h = _host_i32(cu_seqlens_host)
+    n, gd, gh, _keep = _grp(groups_dev, groups_host)
+    _check(lib.dualkv_bwd_groups(C.byref(shape), n, gd, gh, total_ctx, _tin(do_d), _tin(o_d), _ptr(lse_d), _tin(q_d),
+                                 _tin(k_c), _tin(v_c), _tin(k_d), _tin(v_d), _ptr(cu_seqlens_dev),
+                                 h[0] if h else None, _tout(dq_d), _tout(dk_c), _tout(dv_c), _tout(dk_d), _tout(dv_d),
+                                 _ptr(dk_c_acc32), _ptr(dv_c_acc32), wp, wb, _stream()), "dualkv_bwd_groups")
 
 
 def dualkv_zero_ctx_grads(shape, dk_c_acc32, dv_c_acc32):

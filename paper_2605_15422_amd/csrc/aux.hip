@@ -80,6 +80,41 @@ hipError_t launch_fill_f32(float* ptr, int64_t n, float value, hipStream_t st) {
 }
 
 // ---------------------------------------------------------------------------------------------
+// Several prompt groups in one launch: per-sequence {first prompt row, prompt length} from the group table
+// {first prompt row, P_g, first sequence, end sequence}; one thread per (group, sequence slot).
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void expand_groups_kernel(const int32_t* __restrict__ grp, int n_groups,
+                                                            int32_t* __restrict__ seq_ctx) {
+  const int g = blockIdx.y;
+  if (g >= n_groups) return;
+  const int s0 = grp[4 * g + 2], s1 = grp[4 * g + 3];
+  for (int s = s0 + blockIdx.x * 256 + threadIdx.x; s < s1; s += gridDim.x * 256) {
+    seq_ctx[2 * s] = grp[4 * g];
+    seq_ctx[2 * s + 1] = grp[4 * g + 1];
+  }
+}
+
+// prompt offsets (n + 1) of groups packed back to back: the groups' first rows, then the total
+__global__ __launch_bounds__(256) void group_offsets_kernel(const int32_t* __restrict__ grp, int n_groups, int total_ctx,
+                                                            int32_t* __restrict__ cu) {
+  for (int g = blockIdx.x * 256 + threadIdx.x; g <= n_groups; g += gridDim.x * 256) cu[g] = g < n_groups ? grp[4 * g] : total_ctx;
+}
+
+hipError_t launch_group_offsets(const int32_t* grp, int n_groups, int total_ctx, int32_t* cu, hipStream_t st) {
+  hipLaunchKernelGGL(group_offsets_kernel, dim3((unsigned)min(64, (n_groups + 256) / 256)), dim3(256), 0, st, grp, n_groups,
+                     total_ctx, cu);
+  return hipGetLastError();
+}
+
+hipError_t launch_expand_groups(const int32_t* grp, int n_groups, int n_seqs, int32_t* seq_ctx, hipStream_t st) {
+  if (n_groups <= 0 || n_seqs <= 0) return hipSuccess;
+  const int bx = min(64, (n_seqs + 255) / 256);
+  hipLaunchKernelGGL(expand_groups_kernel, dim3((unsigned)bx, (unsigned)n_groups), dim3(256), 0, st, grp, n_groups,
+                     seq_ctx);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
 // acc (P, Hk, D) fp32 contiguous -> out (P, Hk, D) bf16 strided, multiplied by `mul`
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void convert_ctx_kernel(const float* __restrict__ acc, TViewOut out, int64_t n8,

@@ -188,6 +188,12 @@ struct AttnParams {
   float* dkd_acc;                        // optional fp32 (rows, Hk, d) accumulators for response-region keys
   float* dvd_acc;
   const int32_t* cu;                     // (N+1) or nullptr => one sequence [0, total)
+  // Several prompt groups in one launch (Sec. 2.2): grp = n_groups x {first prompt row, P_g, first sequence, end
+  // sequence} (device), seq_ctx = per sequence {first prompt row, P_g} expanded from it; both nullptr for one group,
+  // whose prompt is rows [0, ctx_len) of kc / vc.  With groups, ctx_len is the largest P_g (grid sizing only).
+  const int32_t* grp;
+  const int32_t* seq_ctx;
+  int n_groups;
   int n_seqs, ctx_len, total, max_rows;
   int H, Hk, G;
   int window;                            // > 0: sliding window

@@ -26,6 +26,7 @@
 #include <type_traits>
 #include "common.h"
 #include "dma.h"
+#include "kvsched.h"
 #include "launch.h"
 #include "tiles.h"
 
@@ -55,36 +56,16 @@ __global__ __launch_bounds__(512) void dkdv4_kernel(const AttnParams p) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, hi = lane >> 5;
   const int kvs = wave & 3;
-  const int P = p.ctx_len, W = p.window;
+  const int W = p.window;
 
-  // ---- block decode: prompt tiles first (heavy), then response tiles
-  const int ctx_blocks = p.n_ctx_tiles * p.Hk * p.n_split;
-  int bid = blockIdx.x;
-  bool is_ctx;
-  int hk, key0, seq_lo, seq_hi;
-  if (bid < ctx_blocks) {
-    is_ctx = true;
-    hk = bid % p.Hk;
-    int t = bid / p.Hk;
-    const int split = t % p.n_split;
-    key0 = (t / p.n_split) * BN;
-    seq_lo = (int)((int64_t)p.n_seqs * split / p.n_split);
-    seq_hi = (int)((int64_t)p.n_seqs * (split + 1) / p.n_split);
-  } else {
-    bid -= ctx_blocks;
-    is_ctx = false;
-    hk = bid % p.Hk;
-    int t = bid / p.Hk;
-    key0 = (t % p.n_dec_tiles) * BN;
-    seq_lo = t / p.n_dec_tiles;
-    seq_hi = seq_lo + 1;
-    const int rb0 = p.cu ? p.cu[seq_lo] : 0;
-    const int Rs = p.cu ? (p.cu[seq_lo + 1] - rb0) : p.total;
-    if (key0 >= Rs) return;
-  }
-  int region_len, key_row_begin = 0;
+  KVBlock kb;
+  if (!decode_kvblock(p, BN, kb)) return;
+  const bool is_ctx = kb.is_ctx;
+  const int hk = kb.hk, key0 = kb.key0, seq_lo = kb.seq_lo, seq_hi = kb.seq_hi, P = kb.P;
+  int region_len, key_row_begin;
   if (is_ctx) {
     region_len = P;
+    key_row_begin = kb.ctx_off;
   } else {
     key_row_begin = p.cu ? p.cu[seq_lo] : 0;
     region_len = p.cu ? (p.cu[seq_lo + 1] - key_row_begin) : p.total;
@@ -97,8 +78,8 @@ __global__ __launch_bounds__(512) void dkdv4_kernel(const AttnParams p) {
     const u16 *kbase, *vbase;
     int64_t kts, vts;
     if (is_ctx) {
-      kbase = p.kc.ptr + (int64_t)hk * p.kc.hs;
-      vbase = p.vc.ptr + (int64_t)hk * p.vc.hs;
+      kbase = p.kc.ptr + (int64_t)key_row_begin * p.kc.ts + (int64_t)hk * p.kc.hs;
+      vbase = p.vc.ptr + (int64_t)key_row_begin * p.vc.ts + (int64_t)hk * p.vc.hs;
       kts = p.kc.ts;
       vts = p.vc.ts;
     } else {
@@ -518,8 +499,8 @@ __global__ __launch_bounds__(512) void dkdv4_kernel(const AttnParams p) {
           unsafeAtomicAdd(acc_k + off, gk);
           unsafeAtomicAdd(acc_v + off, gv);
         } else if (is_ctx) {
-          p.dkc.ptr[(int64_t)key * p.dkc.ts + (int64_t)hk * p.dkc.hs + dcol] = (u16)(pack2_bf16(gk, 0.f) & 0xffffu);
-          p.dvc.ptr[(int64_t)key * p.dvc.ts + (int64_t)hk * p.dvc.hs + dcol] = (u16)(pack2_bf16(gv, 0.f) & 0xffffu);
+          p.dkc.ptr[(int64_t)(key_row_begin + key) * p.dkc.ts + (int64_t)hk * p.dkc.hs + dcol] = (u16)(pack2_bf16(gk, 0.f) & 0xffffu);
+          p.dvc.ptr[(int64_t)(key_row_begin + key) * p.dvc.ts + (int64_t)hk * p.dvc.hs + dcol] = (u16)(pack2_bf16(gv, 0.f) & 0xffffu);
         } else {
           const int64_t grow = key_row_begin + key;
           p.dkd.ptr[grow * p.dkd.ts + (int64_t)hk * p.dkd.hs + dcol] = (u16)(pack2_bf16(gk, 0.f) & 0xffffu);
@@ -544,7 +525,8 @@ static hipError_t launch_dkdv4_t(AttnParams p, hipStream_t st) {
   auto kern = dkdv4_kernel<D, LOCAL>;
   hipError_t e = ensure_dynamic_lds<dkdv4_kernel<D, LOCAL>>(smem);
   if (e != hipSuccess) return e;
-  const int64_t nblk = (int64_t)p.n_ctx_tiles * p.Hk * p.n_split + (int64_t)p.n_seqs * p.n_dec_tiles * p.Hk;
+  const int64_t nblk = (int64_t)(p.grp ? p.n_groups : 1) * p.n_ctx_tiles * p.Hk * p.n_split +
+                       (int64_t)p.n_seqs * p.n_dec_tiles * p.Hk;
   if (nblk == 0) return hipSuccess;
   hipLaunchKernelGGL(kern, dim3((unsigned)nblk), dim3(512), smem, st, p);
   return hipGetLastError();

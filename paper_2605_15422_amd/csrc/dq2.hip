@@ -32,7 +32,7 @@ __global__ __launch_bounds__(512) void dq2_kernel(const AttnParams p) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, hi = lane >> 5;
-  const int P = p.ctx_len, R = b.R, W = p.window;
+  const int P = b.P, R = b.R, W = p.window;
   const float c = p.scale_log2;
 
   const int head = b.hk * p.G + b.hc * p.GP + wave / p.RSH;
@@ -76,8 +76,8 @@ __global__ __launch_bounds__(512) void dq2_kernel(const AttnParams p) {
     toff1[ds] = tr_off<D>(lane, hi * 4 + 8, ds * 32);
   }
 
-  const u16* kc_base = p.kc.ptr + (int64_t)b.hk * p.kc.hs;
-  const u16* vc_base = p.vc.ptr + (int64_t)b.hk * p.vc.hs;
+  const u16* kc_base = p.kc.ptr + (int64_t)b.ctx_off * p.kc.ts + (int64_t)b.hk * p.kc.hs;
+  const u16* vc_base = p.vc.ptr + (int64_t)b.ctx_off * p.vc.ts + (int64_t)b.hk * p.vc.hs;
   const u16* kd_base = p.kd.ptr + (int64_t)b.row_begin * p.kd.ts + (int64_t)b.hk * p.kd.hs;
   const u16* vd_base = p.vd.ptr + (int64_t)b.row_begin * p.vd.ts + (int64_t)b.hk * p.vd.hs;
   const int n_ctx_run = b.n_ctx - b.c0;

@@ -48,7 +48,7 @@ __global__ __launch_bounds__(kFwdWaves * 64) void fwd2_kernel(const AttnParams p
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, hi = lane >> 5;
-  const int P = p.ctx_len, R = b.R, W = p.window;
+  const int P = b.P, R = b.R, W = p.window;
   const float c = p.scale_log2;
 
   const int head = b.hk * p.G + b.hc * p.GP + wave / p.RSH;
@@ -93,8 +93,8 @@ __global__ __launch_bounds__(kFwdWaves * 64) void fwd2_kernel(const AttnParams p
   // LDS chunk position l % CPR of row l / CPR of the instruction and fetches the chunk the swizzle stores
   // there (both swizzles have a period that divides LW RPI rows, so one offset per tensor serves every t).
   // Keys past the end of the region re-read the last key: their scores are masked like any invisible key.
-  const u16* kc_base = p.kc.ptr + (int64_t)b.hk * p.kc.hs;
-  const u16* vc_base = p.vc.ptr + (int64_t)b.hk * p.vc.hs;
+  const u16* kc_base = p.kc.ptr + (int64_t)b.ctx_off * p.kc.ts + (int64_t)b.hk * p.kc.hs;
+  const u16* vc_base = p.vc.ptr + (int64_t)b.ctx_off * p.vc.ts + (int64_t)b.hk * p.vc.hs;
   const u16* kd_base = p.kd.ptr + (int64_t)b.row_begin * p.kd.ts + (int64_t)b.hk * p.kd.hs;
   const u16* vd_base = p.vd.ptr + (int64_t)b.row_begin * p.vd.ts + (int64_t)b.hk * p.vd.hs;
   const int n_ctx_run = b.n_ctx - b.c0;

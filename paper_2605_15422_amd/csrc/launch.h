@@ -13,11 +13,14 @@ hipError_t launch_dkdv(const AttnParams& p, int head_dim, hipStream_t st);
 // tuned backward kernels for head dims 64 / 128
 hipError_t launch_dq2(const AttnParams& p, int head_dim, hipStream_t st);
 hipError_t launch_dkdv4(const AttnParams& p, int head_dim, hipStream_t st);
+hipError_t launch_dkdv5(const AttnParams& p, int head_dim, hipStream_t st);
 // key tile (rows of K/V owned by one workgroup) of the dK/dV kernel for a head dim
 int dkdv_key_tile(int head_dim);
 
 hipError_t launch_dot_do_o(const TView& dout, const TView& o, const float* lse, float* dvec, float* lse2, int total,
                            int H, int head_dim, hipStream_t st);
+hipError_t launch_group_offsets(const int32_t* grp, int n_groups, int total_ctx, int32_t* cu, hipStream_t st);
+hipError_t launch_expand_groups(const int32_t* grp, int n_groups, int n_seqs, int32_t* seq_ctx, hipStream_t st);
 hipError_t launch_fill_f32(float* ptr, int64_t n, float value, hipStream_t st);
 hipError_t launch_convert_ctx(const float* acc, const TViewOut& out, int P, int Hk, int head_dim, float mul,
                               hipStream_t st);

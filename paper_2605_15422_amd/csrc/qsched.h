@@ -11,6 +11,7 @@ namespace dkv {
 // ---------------------------------------------------------------------------------------------
 struct QBlock {
   int hk, hc, mb, seq, row_begin, R, blk_row0;
+  int P, ctx_off;   // prompt length and first prompt row of the sequence's group
   int c0, n_ctx, d0, n_dec, n_tiles;
 };
 
@@ -25,7 +26,9 @@ __device__ __forceinline__ bool decode_qblock(const AttnParams& p, QBlock& b) {
   b.R = p.cu ? (p.cu[b.seq + 1] - b.row_begin) : p.total;
   b.blk_row0 = b.mb * p.BMR;
   if (b.blk_row0 >= b.R) return false;
-  const int P = p.ctx_len;
+  b.P = p.seq_ctx ? p.seq_ctx[2 * b.seq + 1] : p.ctx_len;
+  b.ctx_off = p.seq_ctx ? p.seq_ctx[2 * b.seq] : 0;
+  const int P = b.P;
   const int last_row = min(b.R, b.blk_row0 + p.BMR) - 1;
   b.n_ctx = (P + BN - 1) / BN;
   b.n_dec = last_row / BN + 1;

@@ -49,7 +49,7 @@ __global__ __launch_bounds__(NW * 64) void fwd_kernel(const AttnParams p) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, hi = lane >> 5;
   const int dp = wave % DSPLIT, rg = wave / DSPLIT;
-  const int P = p.ctx_len, R = b.R, W = p.window;
+  const int P = b.P, R = b.R, W = p.window;
   const float c = p.scale_log2;
 
   int head[QSUB], row0[QSUB];
@@ -86,8 +86,8 @@ __global__ __launch_bounds__(NW * 64) void fwd_kernel(const AttnParams p) {
       for (int r = 0; r < 16; ++r) oacc[qs][ds][r] = 0.f;
   }
 
-  const u16* kc_base = p.kc.ptr + (int64_t)b.hk * p.kc.hs;
-  const u16* vc_base = p.vc.ptr + (int64_t)b.hk * p.vc.hs;
+  const u16* kc_base = p.kc.ptr + (int64_t)b.ctx_off * p.kc.ts + (int64_t)b.hk * p.kc.hs;
+  const u16* vc_base = p.vc.ptr + (int64_t)b.ctx_off * p.vc.ts + (int64_t)b.hk * p.vc.hs;
   const u16* kd_base = p.kd.ptr + (int64_t)b.row_begin * p.kd.ts + (int64_t)b.hk * p.kd.hs;
   const u16* vd_base = p.vd.ptr + (int64_t)b.row_begin * p.vd.ts + (int64_t)b.hk * p.vd.hs;
   const int n_ctx_run = b.n_ctx - b.c0;
@@ -266,7 +266,7 @@ __global__ __launch_bounds__(NW * 64) void dq_kernel(const AttnParams p) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, hi = lane >> 5;
   const int dp = wave % DSPLIT, rg = wave / DSPLIT;
-  const int P = p.ctx_len, R = b.R, W = p.window;
+  const int P = b.P, R = b.R, W = p.window;
   const float c = p.scale_log2;
 
   int head[QSUB], row0[QSUB];
@@ -306,8 +306,8 @@ __global__ __launch_bounds__(NW * 64) void dq_kernel(const AttnParams p) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) dqacc[qs][ds][r] = 0.f;
 
-  const u16* kc_base = p.kc.ptr + (int64_t)b.hk * p.kc.hs;
-  const u16* vc_base = p.vc.ptr + (int64_t)b.hk * p.vc.hs;
+  const u16* kc_base = p.kc.ptr + (int64_t)b.ctx_off * p.kc.ts + (int64_t)b.hk * p.kc.hs;
+  const u16* vc_base = p.vc.ptr + (int64_t)b.ctx_off * p.vc.ts + (int64_t)b.hk * p.vc.hs;
   const u16* kd_base = p.kd.ptr + (int64_t)b.row_begin * p.kd.ts + (int64_t)b.hk * p.kd.hs;
   const u16* vd_base = p.vd.ptr + (int64_t)b.row_begin * p.vd.ts + (int64_t)b.hk * p.vd.hs;
   const int n_ctx_run = b.n_ctx - b.c0;

@@ -1,0 +1,186 @@
+"""Several prompt groups in ONE call of the *_groups entry points (Sec. 2.2, "multiple groups") against the fp64
+oracle evaluated group by group: heterogeneous prompt lengths (including P_g = 0), a group without sequences,
+empty responses, both gradient modes, tuned and generic kernels, with and without a window."""
+import numpy as np
+import pytest
+
+from oracle import attention_oracle as orc
+from paper_2605_15422_amd import workloads as W
+
+import parity_util as PU
+
+pytestmark = pytest.mark.gpu
+
+
+def _build(specs, H, Hk, d, window, seed):
+    """specs: list of (P_g, response lengths).  Returns per-group workloads and the packed arrays / tables."""
+    wls = []
+    for g, (P, lens) in enumerate(specs):
+        shape = W.Shape("grp%d" % g, max(len(lens), 1), P, 0, 0, H, Hk, d, window, seed=seed + 17 * g)
+        # a group without sequences is given one empty response on the oracle side: its prompt pass is unchanged
+        wls.append(W.make_workload(shape, resp_lens=np.asarray(lens if len(lens) else [0])))
+    cat = lambda name: np.concatenate([getattr(w, name) for w in wls], axis=0)
+    packed = {n: cat(n) for n in ("q_c", "k_c", "v_c", "do_c", "q_d", "k_d", "v_d", "do_d")}
+    table, cu = [], [0]
+    ctx_off = seq = 0
+    for (P, lens) in specs:
+        table.append((ctx_off, P, seq, seq + len(lens)))
+        ctx_off += P
+        seq += len(lens)
+        for r in lens:
+            cu.append(cu[-1] + int(r))
+    return wls, packed, np.asarray(table, dtype=np.int32).reshape(-1, 4), np.asarray(cu, dtype=np.int32)
+
+
+def _oracle(wls, window):
+    refs = []
+    for w in wls:
+        x = PU.oracle_inputs(w)
+        refs.append(orc.dualkv_reference(x["q_c"], x["k_c"], x["v_c"], x["q_d"], x["k_d"], x["v_d"], w.cu_seqlens, w.scale,
+                                         x["do_c"], x["do_d"], window))
+    return refs
+
+
+def _run_groups(specs, packed, table, cu, H, Hk, d, window, flags):
+    import torch
+    from paper_2605_15422_amd import binding as B
+    dev = {k: B.bf16_from_bits(v) for k, v in packed.items()}
+    n_seqs = len(cu) - 1
+    total_ctx, T = int(packed["q_c"].shape[0]), int(cu[-1])
+    lens = np.diff(cu)
+    max_p = max(P for P, _ in specs)
+    shp = B.make_shape(max(n_seqs, 1), max_p, T, int(lens.max()) if n_seqs else 0, H, Hk, d, window, 0.0, flags)
+    g_dev = torch.from_numpy(table.copy()).cuda()
+    cu_dev = torch.from_numpy(cu.copy()).cuda()
+
+    def ws(op):
+        n = B.dualkv_groups_workspace_bytes(shp, len(specs), total_ctx, op)
+        return torch.full((max(n, 16),), 0xFF, dtype=torch.uint8, device="cuda")
+
+    def nan_like(t):
+        x = torch.empty_like(t)
+        x.view(torch.int16).fill_(0x7FC0)
+        return x
+
+    out = dict(o_c=nan_like(dev["q_c"]), o_d=nan_like(dev["q_d"]), dq_c=nan_like(dev["q_c"]), dq_d=nan_like(dev["q_d"]),
+               dk_d=nan_like(dev["k_d"]), dv_d=nan_like(dev["v_d"]),
+               lse_c=torch.full((H, total_ctx), float("nan"), device="cuda"),
+               lse_d=torch.full((H, T), float("nan"), device="cuda"))
+    acc = bool(flags & B.FLAG_ACCUM_CTX_F32)
+    if acc:
+        out["dk_c_acc"] = torch.full(dev["k_c"].shape, float("nan"), dtype=torch.float32, device="cuda")
+        out["dv_c_acc"] = torch.full(dev["v_c"].shape, float("nan"), dtype=torch.float32, device="cuda")
+        out["dk_c"], out["dv_c"] = nan_like(dev["k_c"]), nan_like(dev["v_c"])
+        shp_all = B.make_shape(1, total_ctx, 0, 0, H, Hk, d, window, 0.0, flags)
+        B.dualkv_zero_ctx_grads(shp_all, out["dk_c_acc"], out["dv_c_acc"])
+    else:
+        for n in ("dk_c1", "dv_c1", "dk_c2", "dv_c2"):
+            out[n] = nan_like(dev["k_c"])
+    B.dualkv_ctx_fwd_groups(shp, g_dev, table, total_ctx, dev["q_c"], dev["k_c"], dev["v_c"], out["o_c"], out["lse_c"],
+                            ws(B.OP_CTX_FWD))
+    B.dualkv_fwd_groups(shp, g_dev, table, total_ctx, dev["q_d"], dev["k_c"], dev["v_c"], dev["k_d"], dev["v_d"], cu_dev,
+                        cu, out["o_d"], out["lse_d"], ws(B.OP_FWD))
+    B.dualkv_bwd_groups(shp, g_dev, table, total_ctx, dev["do_d"], out["o_d"], out["lse_d"], dev["q_d"], dev["k_c"],
+                        dev["v_c"], dev["k_d"], dev["v_d"], cu_dev, cu, out["dq_d"],
+                        None if acc else out["dk_c2"], None if acc else out["dv_c2"], out["dk_d"], out["dv_d"],
+                        out.get("dk_c_acc"), out.get("dv_c_acc"), ws(B.OP_BWD))
+    B.dualkv_ctx_bwd_groups(shp, g_dev, table, total_ctx, dev["do_c"], out["o_c"], out["lse_c"], dev["q_c"], dev["k_c"],
+                            dev["v_c"], out["dq_c"], None if acc else out["dk_c1"], None if acc else out["dv_c1"],
+                            out.get("dk_c_acc"), out.get("dv_c_acc"), ws(B.OP_CTX_BWD))
+    if acc:
+        B.dualkv_finalize_ctx_grads(shp_all, out["dk_c_acc"], out["dv_c_acc"], out["dk_c"], out["dv_c"])
+    torch.cuda.synchronize()
+    return dev, out
+
+
+CASES = [
+    # name, H, Hk, d, window, specs
+    ("d128_mixed", 8, 2, 128, 0, [(100, [40, 17, 64]), (0, [33, 5]), (257, []), (64, [1, 0, 130])]),
+    ("d64_window", 4, 2, 64, 37, [(150, [120, 0]), (31, [200]), (0, [70])]),
+    ("d128_many_small", 4, 4, 128, 0, [(33, [5, 9]), (1, [1]), (129, [64, 64, 64]), (200, [3]), (7, [0, 0]), (90, [31, 33])]),
+    ("d256_generic", 4, 2, 256, 0, [(130, [64, 31]), (0, [20]), (65, [])]),
+    ("d512_generic", 2, 1, 512, 0, [(65, [33, 70]), (40, [9])]),
+    ("d96_window", 2, 2, 96, 40, [(130, [90, 33]), (50, [64])]),
+]
+
+
+@pytest.mark.parametrize("flags", [0, 1], ids=["two_terms", "joint_fp32"])
+@pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
+def test_groups_in_one_call_match_the_oracle_group_by_group(case, flags):
+    name, H, Hk, d, window, specs = case
+    print("case groups", name, flags, flush=True)
+    wls, packed, table, cu = _build(specs, H, Hk, d, window, seed=5100 + len(name))
+    refs = _oracle(wls, window)
+    dev, out = _run_groups(specs, packed, table, cu, H, Hk, d, window, flags)
+    rep = []
+    try:
+        seq = 0
+        for g, ((P, lens), ref) in enumerate(zip(specs, refs)):
+            c0 = int(table[g, 0])
+            r0, r1 = int(cu[seq]), int(cu[seq + len(lens)])
+            seq += len(lens)
+            tag = "g%d " % g
+            cs, rs = slice(c0, c0 + P), slice(r0, r1)
+            PU.compare(tag + "O_c", PU.to_f64(out["o_c"][cs]), ref["o_c"], rep)
+            PU.compare_lse(tag + "LSE_c", PU.to_f64(out["lse_c"][:, cs]), ref["lse_c"], rep)
+            PU.compare(tag + "dQ_c", PU.to_f64(out["dq_c"][cs]), ref["call1"]["dq_c"], rep)
+            if len(lens):
+                PU.compare(tag + "O_d", PU.to_f64(out["o_d"][rs]), ref["o_d"], rep)
+                PU.compare_lse(tag + "LSE_d", PU.to_f64(out["lse_d"][:, rs]), ref["lse_d"], rep)
+                for n in ("dq_d", "dk_d", "dv_d"):
+                    PU.compare(tag + n, PU.to_f64(out[n][rs]), ref["call2"][n], rep)
+            if flags & 1:
+                for n in ("dk_c", "dv_c"):
+                    PU.compare(tag + n + "32", PU.to_f64(out[n + "_acc"][cs]), ref["total"][n], rep)
+                    PU.compare(tag + n, PU.to_f64(out[n][cs]), ref["total"][n], rep)
+            else:
+                for n in ("dk_c", "dv_c"):
+                    PU.compare(tag + n + "(2)", PU.to_f64(out[n + "2"][cs]), ref["call2"][n], rep)
+                    PU.compare(tag + n + "(1)", PU.to_f64(out[n + "1"][cs]), ref["call1"][n], rep)
+    finally:
+        print("\n[groups %s flags=%d]\n  " % (name, flags) + "\n  ".join(rep), flush=True)
+
+
+def test_groups_call_equals_the_per_group_calls_bit_for_bit():
+    """Outputs that involve no atomics are the same bits whether the groups go through one *_groups call or through one
+    single-group call each (same kernels, same tiles, same summation order)."""
+    import torch
+    from paper_2605_15422_amd import binding as B, runner
+    H, Hk, d, window = 8, 2, 128, 0
+    specs = [(300, [90, 260]), (64, [128]), (517, [131, 70, 1])]
+    wls, packed, table, cu = _build(specs, H, Hk, d, window, seed=6200)
+    dev, out = _run_groups(specs, packed, table, cu, H, Hk, d, window, 0)
+    seq = 0
+    for g, ((P, lens), wl) in enumerate(zip(specs, wls)):
+        dg = B.upload(wl)
+        b = runner.alloc(dg)
+        runner.layer_step(dg, b)
+        torch.cuda.synchronize()
+        c0 = int(table[g, 0])
+        cs, rs = slice(c0, c0 + P), slice(int(cu[seq]), int(cu[seq + len(lens)]))
+        seq += len(lens)
+        for n, sl in (("o_c", cs), ("dq_c", cs), ("o_d", rs), ("dq_d", rs), ("dk_d", rs), ("dv_d", rs)):
+            assert torch.equal(out[n][sl].view(torch.int16), getattr(b, n).view(torch.int16)), (g, n)
+        assert torch.equal(out["lse_c"][:, cs], b.lse_c) and torch.equal(out["lse_d"][:, rs], b.lse_d), g
+
+
+def test_group_table_validation_on_the_host():
+    import ctypes as C
+    from paper_2605_15422_amd import binding as B
+    shp = B.make_shape(3, 100, 50, 30, 4, 2, 128)
+    null, nullo = B.TIn(None, 0, 0), B.TOut(None, 0, 0)
+
+    def rc(table, total_ctx=150):
+        t = np.asarray(table, dtype=np.int32).reshape(-1, 4)
+        fake_dev = C.c_void_p(0x1000)
+        return B.lib.dualkv_fwd_groups(C.byref(shp), len(t), fake_dev, t.ctypes.data_as(C.c_void_p), total_ctx, null, null,
+                                       null, null, null, None, None, nullo, None, None, 0, None)
+
+    assert rc([(0, 100, 0, 2), (100, 50, 2, 3)]) == B.E_INVALID      # passes the table, then NULL tensors
+    assert rc([(0, 100, 0, 2), (100, 50, 1, 3)]) == B.E_INVALID      # sequence ranges overlap
+    assert rc([(0, 100, 0, 2)]) == B.E_INVALID                        # sequences 2.. not covered
+    assert rc([(0, 101, 0, 3)]) == B.E_INVALID                        # P_g above shape.ctx_len
+    assert rc([(100, 60, 0, 3)]) == B.E_INVALID                       # prompt beyond total_ctx
+    assert B.lib.dualkv_fwd_groups(C.byref(shp), 0, None, None, 0, null, null, null, null, null, None, None, nullo, None,
+                                   None, 0, None) == B.E_INVALID
+    assert B.dualkv_groups_workspace_bytes(shp, 2, 150, B.OP_FWD) >= 3 * 8
