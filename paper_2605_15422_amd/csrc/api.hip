@@ -1,7 +1,6 @@
 // C ABI of the library (include/dualkv.h): host-side validation, workspace carving and dispatch.
 // Nothing here touches device memory except through kernel launches on the caller's stream.
 #include <cstdlib>
-#include <cstring>
 #include <mutex>
 #include "../../include/dualkv.h"
 
@@ -154,23 +153,8 @@ hipError_t run_dq(const AttnParams& p, int d, hipStream_t st) {
   if (d == 64 || d == 128) return dkv::launch_dq2(p, d, st);
   return dkv::launch_dq(p, d, st);
 }
-// Debug override: DUALKV_FORCE_VARIANT="dkdv=4,dq=2" selects an alternative kernel for a stage (tests and A/B timing);
-// unknown keys and values fall back to the default.  Read on every call, so a test can flip it inside one process.
-int forced_variant(const char* key) {
-  const char* env = getenv("DUALKV_FORCE_VARIANT");
-  if (env == nullptr) return 0;
-  const size_t kl = strlen(key);
-  for (const char* p = env; *p;) {
-    if (strncmp(p, key, kl) == 0 && p[kl] == '=') return atoi(p + kl + 1);
-    const char* c = strchr(p, ',');
-    if (c == nullptr) break;
-    p = c + 1;
-  }
-  return 0;
-}
-
 hipError_t run_dkdv(const AttnParams& p, int d, hipStream_t st) {
-  if (d == 64 || d == 128) return forced_variant("dkdv") == 5 ? dkv::launch_dkdv5(p, d, st) : dkv::launch_dkdv4(p, d, st);
+  if (d == 64 || d == 128) return dkv::launch_dkdv4(p, d, st);
   return dkv::launch_dkdv(p, d, st);
 }
 

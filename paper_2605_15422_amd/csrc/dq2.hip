@@ -147,51 +147,45 @@ __global__ __launch_bounds__(512) void dq2_kernel(const AttnParams p) {
       if (!active) continue;
       const unsigned char* kh = Kb + half * 32 * RB;
       const unsigned char* vh = Vb + half * 32 * RB;
-      // S^T = K Q^T and dP^T - D = V dO^T - D (accumulator initialised to -D).  All 2 KS operand reads are
-      // requested first, in two groups; each group's MFMAs consume their operands in the reverse of the
-      // request order, so ONE wait per group covers them (an instruction of any kind costs the SIMD about
-      // as much issue time as a sixth of an MFMA: sixteen waits are not free).
+      // S^T = K Q^T first, complete, then dP^T - D = V dO^T - D (accumulator initialised to -D): the exponentials of
+      // S^T issue in the shadow of the dP MFMAs (two per MFMA), only the products and the packing are left after them.
+      // The K operands are requested before the V operands, so the S chain starts as soon as its own have landed.
       bf16x8 ko[KS], vo[KS];
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        ko[ks] = *reinterpret_cast<const bf16x8*>(kh + roff[ks]);
-        vo[ks] = *reinterpret_cast<const bf16x8*>(vh + roff[ks]);
-      }
+      for (int ks = 0; ks < KS; ++ks) ko[ks] = *reinterpret_cast<const bf16x8*>(kh + roff[ks]);
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) vo[ks] = *reinterpret_cast<const bf16x8*>(vh + roff[ks]);
       __builtin_amdgcn_sched_barrier(0);
       f32x16 s, dpt;
-      constexpr int G = KS / 2;
+      // S chain first (complete before the dP chain starts) ...
 #pragma unroll
-      for (int g = 0; g < 2; ++g)
+      for (int r = 0; r < 16; ++r) s[r] = 0.f;
 #pragma unroll
-        for (int q = G - 1; q >= 0; --q) {
-          const int ks = g * G + q;
-          if (g == 0 && q == G - 1) {
-            f32x16 z;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) z[r] = 0.f;
-            dpt = mfma32(vo[ks], dof[ks], negd);
-            s = mfma32(ko[ks], qf[ks], z);
-          } else {
-            dpt = mfma32(vo[ks], dof[ks], dpt);
-            s = mfma32(ko[ks], qf[ks], s);
-          }
-        }
+      for (int ks = 0; ks < KS; ++ks) s = mfma32(ko[ks], qf[ks], s);
       __builtin_amdgcn_sched_barrier(0);
+      // ... so that the exponentials of S issue in the shadow of the dP MFMAs
       const bool need = !plain && tile_needs_mask<LOCAL, 32>(is_ctx, key0, row0, P, R, W);
-      float dsv[16];
-      // two straight-line variants: a per-element test of a run-time flag costs three branches per element
+      float ev[16], dsv[16];
+      constexpr int EPM = 16 / KS;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        dpt = mfma32(vo[ks], dof[ks], ks == 0 ? negd : dpt);
+#pragma unroll
+        for (int e = ks * EPM; e < (ks + 1) * EPM; ++e) {
+          ev[e] = __builtin_amdgcn_exp2f(s[e] * c - lse2);
+          asm volatile("" : "+v"(ev[e]));
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
       if (__builtin_expect(need, 0)) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          float e = __builtin_amdgcn_exp2f(s[r] * c - lse2);
           const int key = key0 + crow(r, hi);
-          if (!visible<LOCAL>(is_ctx, key, row, P, R, W)) e = 0.f;
-          dsv[r] = e * dpt[r];   // dS^T
+          if (!visible<LOCAL>(is_ctx, key, row, P, R, W)) ev[r] = 0.f;
         }
-      } else {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) dsv[r] = __builtin_amdgcn_exp2f(s[r] * c - lse2) * dpt[r];
       }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) dsv[r] = ev[r] * dpt[r];   // dS^T
       // dQ^T += K^T dS^T
 #pragma unroll
       for (int t2 = 0; t2 < 2; ++t2) {
