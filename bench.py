@@ -414,6 +414,7 @@ def main():
     ap.add_argument("--no-ncopy", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-others", action="store_true", help="skip the other benchmark configs")
+    ap.add_argument("--no-alt", action="store_true", help="skip the short run in the other gradient mode")
     ap.add_argument("--two-terms", action="store_true",
                     help="time the mode that returns the Call-1 and Call-2 terms of dK_c / dV_c as two bf16 tensors "
                          "(the paper's interface) instead of the fp32 joint accumulation with one cast")
@@ -442,10 +443,12 @@ def main():
 
     ms, wall_ms, stage = time_layer(dg, bufs, args.steps, args.warmup)
     # the other mode, for reference (fewer steps)
-    dg_alt = B.upload(wl, B.FLAG_ACCUM_CTX_F32 if args.two_terms else 0)
-    bufs_alt = runner.alloc(dg_alt, poison=False)
-    ms_alt, _, _ = time_layer(dg_alt, bufs_alt, max(3, args.steps // 3), 1)
-    del dg_alt, bufs_alt
+    ms_alt = None
+    if not args.no_alt:
+        dg_alt = B.upload(wl, B.FLAG_ACCUM_CTX_F32 if args.two_terms else 0)
+        bufs_alt = runner.alloc(dg_alt, poison=False)
+        ms_alt, _, _ = time_layer(dg_alt, bufs_alt, max(3, args.steps // 3), 1)
+        del dg_alt, bufs_alt
 
     # dominant kernel and its roofline (MFMA bound: algorithmic flops of that kernel / its duration)
     d, H = shape.head_dim, shape.n_q_heads
@@ -483,7 +486,7 @@ def main():
         "bwd_ms": round(sum(v for k, v in stage.items() if k not in ("ctx_fwd", "fwd")), 4),
         "ctx_grad_mode": ("two bf16 terms (Call 1, Call 2), summed by the caller" if args.two_terms else
                           "fp32 joint accumulation of Call 1 + Call 2, one cast (Eq. 6 inside the timed step)"),
-        ("ms_per_step_joint_fp32" if args.two_terms else "ms_per_step_two_terms"): round(ms_alt, 4),
+        ("ms_per_step_joint_fp32" if args.two_terms else "ms_per_step_two_terms"): (round(ms_alt, 4) if ms_alt else None),
         "roofline": roofline,
         "ncopy_flop_ratio": round(fl["ncopy"] / fl["layer"], 3),   # FLOPs of N-copy attention over this layer's
     }
