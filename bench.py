@@ -510,6 +510,9 @@ def main():
         out["other_configs"] = time_other_configs(["cfg1_tiny", "cfg3_ragged", "cfg4_30b", "cfg5b_swa", "cfg5a_global"], flags)
     if args.graph_groups > 0:
         out["multi_group"] = time_groups(shape, args.graph_groups, max(args.steps, 20))
+    elif not args.no_others and args.config == "cfg2_qwen8b":
+        # several prompt groups in one call (Sec. 2.2): eight groups of config 1
+        out["multi_group"] = time_groups(W.CONFIGS["cfg1_tiny"], 8, 20)
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(out), flush=True)

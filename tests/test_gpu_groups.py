@@ -184,3 +184,67 @@ def test_group_table_validation_on_the_host():
     assert B.lib.dualkv_fwd_groups(C.byref(shp), 0, None, None, 0, null, null, null, null, null, None, None, nullo, None,
                                    None, 0, None) == B.E_INVALID
     assert B.dualkv_groups_workspace_bytes(shp, 2, 150, B.OP_FWD) >= 3 * 8
+
+
+def test_large_groups_take_the_unsplit_prompt_tile_path():
+    """Groups of realistic size (hundreds of prompt tiles: every prompt tile is owned by ONE workgroup that sums all the
+    sequences and heads of its group in registers and writes bf16 directly, no atomics): the *_groups call must then
+    reproduce the per-group calls bit for bit on EVERY output, including the shared-prompt gradients, with prompt
+    lengths that differ by 4x, a group without sequences and ragged responses."""
+    import torch
+    from paper_2605_15422_amd import binding as B, runner
+    H, Hk, d, window = 16, 8, 128, 0
+    specs = [(8192, [700, 1024, 333]), (2048, [1500]), (4100, []), (16384, [64, 2000, 1, 900])]
+    print("case large groups", flush=True)
+    wls, packed, table, cu = _build(specs, H, Hk, d, window, seed=7300)
+    dev, out = _run_groups(specs, packed, table, cu, H, Hk, d, window, 0)
+    seq = 0
+    for g, ((P, lens), wl) in enumerate(zip(specs, wls)):
+        dg = B.upload(wl)
+        b = runner.alloc(dg)
+        runner.layer_step(dg, b)
+        torch.cuda.synchronize()
+        c0 = int(table[g, 0])
+        cs, rs = slice(c0, c0 + P), slice(int(cu[seq]), int(cu[seq + len(lens)]))
+        seq += len(lens)
+        names = [("o_c", cs), ("dq_c", cs), ("dk_c1", cs), ("dv_c1", cs)]
+        if len(lens):
+            names += [("o_d", rs), ("dq_d", rs), ("dk_d", rs), ("dv_d", rs)]
+        for n, sl in names:
+            assert torch.equal(out[n][sl].view(torch.int16), getattr(b, n).view(torch.int16)), (g, n)
+        # a per-group call of a short prompt (fewer than 512 prompt-tile workgroups) cuts its sequence loop and sums
+        # with fp32 atomics; the long prompts are summed in registers in both routes: same bits
+        unsplit_alone = (P + 127) // 128 * Hk >= 512
+        for n in ("dk_c2", "dv_c2") if len(lens) else ():
+            a, c = out[n][cs].float(), getattr(b, n).float()
+            if unsplit_alone:
+                assert torch.equal(a, c), (g, n)
+            else:
+                assert float((a - c).norm()) <= 1e-2 * float(c.norm()), (g, n)
+        assert torch.equal(out["lse_c"][:, cs], b.lse_c), g
+        if len(lens):
+            assert torch.equal(out["lse_d"][:, rs], b.lse_d), g
+        else:   # no sequence attends to this prompt: its Call-2 gradients are exact zeros
+            assert float(out["dk_c2"][cs].float().abs().max()) == 0.0 and float(out["dv_c2"][cs].float().abs().max()) == 0.0
+    # sampled rows of the largest group against the oracle's one-row evaluation (Eq. 4)
+    rng = np.random.default_rng(5)
+    g, (P, lens), wl = 3, specs[3], wls[3]
+    c0, r0 = int(table[g, 0]), int(cu[4])
+    f = W.bf16_bits_to_f64
+    k_c, v_c, k_d, v_d = f(wl.k_c[:, :1]), f(wl.v_c[:, :1]), f(wl.k_d[:, :1]), f(wl.v_d[:, :1])
+    q_d, do_d = f(wl.q_d[:, :2]), f(wl.do_d[:, :2])
+    got_o, ref_o, got_l, ref_l, got_q, ref_q = [], [], [], [], [], []
+    for _ in range(12):
+        i = int(rng.choice([0, 1, 3]))
+        r = int(rng.integers(0, lens[i]))
+        hh = int(rng.integers(0, 2))
+        row = int(wl.cu_seqlens[i]) + r
+        o, lse, dq = orc.response_row(q_d, k_c, v_c, k_d, v_d, wl.cu_seqlens, wl.scale, i, r, hh, 0, do_row=do_d[row, hh])
+        ref_o.append(o); ref_l.append(lse); ref_q.append(dq)
+        got_o.append(PU.to_f64(out["o_d"][r0 + row, hh])); got_l.append(float(out["lse_d"][hh, r0 + row]))
+        got_q.append(PU.to_f64(out["dq_d"][r0 + row, hh]))
+    rep = []
+    PU.compare("O_d", np.array(got_o), np.array(ref_o), rep)
+    PU.compare_lse("LSE_d", np.array(got_l), np.array(ref_l), rep)
+    PU.compare("dQ_d", np.array(got_q), np.array(ref_q), rep)
+    print("\n  " + "\n  ".join(rep), flush=True)

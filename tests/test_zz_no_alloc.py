@@ -90,6 +90,44 @@ def test_noalloc_matches_workspace_call_twice_second_smaller(flags):
             _check("%s round %d" % (name, rnd), r, g)
 
 
+def test_noalloc_inside_a_captured_graph():
+    """The callers this entry point is for: the call is captured once in a HIP graph (after a first eager call has
+    resolved the scratch address) and replayed; every replay, with eager work and new inputs in between, must equal
+    the eager dualkv_bwd result on the same inputs."""
+    import torch
+    from paper_2605_15422_amd import binding as B
+    print("case noalloc graph", flush=True)
+    shape = W.Shape("na_graph", 3, 300, 0, 0, 8, 2, 128, 0, seed=3310)
+    wl = W.make_workload(shape, resp_lens=np.asarray([90, 200, 33]))
+    dg, b = _layer(wl, 0)
+    s = dg.shape_c
+    outs = {n: torch.empty_like(t) for n, t in (("dq", dg.q_d), ("dkc", dg.k_c), ("dvc", dg.v_c), ("dkd", dg.k_d),
+                                                ("dvd", dg.v_d))}
+
+    def call():
+        B.dualkv_bwd_noalloc(s, dg.do_d, b.o_d, b.lse_d, dg.q_d, dg.k_c, dg.v_c, dg.k_d, dg.v_d, dg.cu_dev, None,
+                             outs["dq"], outs["dkc"], outs["dvc"], outs["dkd"], outs["dvd"])
+
+    call()                       # first use on this device: looks the scratch address up, outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        call()
+    for rep in range(3):
+        if rep:                  # new inputs in the same buffers
+            dg.do_d.copy_(torch.roll(dg.do_d, rep, 0))
+            dg.k_c.copy_(torch.roll(dg.k_c, rep, 0))
+            from paper_2605_15422_amd import runner
+            runner.forward(dg, b)
+        ref = _bwd(dg, b, 0, noalloc=False)
+        for t in outs.values():
+            t.view(torch.int16).fill_(0x7FC0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        _check("graph replay %d" % rep, ref, outs)
+
+
 def test_noalloc_rejects_shapes_beyond_the_static_scratch():
     from paper_2605_15422_amd import binding as B
     # 2 x (rows x H x 4 B) > 32 MiB
