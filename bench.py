@@ -170,6 +170,44 @@ def time_other_configs(names, flags, steps=2, warmup=1):
     return out
 
 
+def time_fused_calls(dg, steps, warmup):
+    """Call 1 and Call 2 in ONE launch per stage: the prompt enters the *_groups entry points as a group of its own
+    (a plain causal sequence without a shared prefix, P_g = 0) next to the group of the N responses, with prompt and
+    response rows in one packed buffer.  Two-term mode: total dK_c = Call-1 rows of dK_d + Call-2 dK_c."""
+    import numpy as np
+    import torch
+    from paper_2605_15422_amd import binding as B
+    s = dg.shape_c
+    P, T, N, H, Hk, d = s.ctx_len, s.total_resp, s.n_seqs, s.n_q_heads, s.n_kv_heads, s.head_dim
+    cat = lambda a, b: torch.cat([a, b], dim=0)
+    q, k, v, do = cat(dg.q_c, dg.q_d), cat(dg.k_c, dg.k_d), cat(dg.v_c, dg.v_d), cat(dg.do_c, dg.do_d)
+    cu = np.concatenate([[0], P + np.asarray(dg.cu_host, dtype=np.int64)]).astype(np.int32)
+    table = np.asarray([(0, 0, 0, 1), (0, P, 1, N + 1)], dtype=np.int32)
+    shp = B.make_shape(N + 1, P, P + T, int(np.diff(cu).max()), H, Hk, d, s.window, s.softmax_scale, 0)
+    g_dev, cu_dev = torch.from_numpy(table).cuda(), torch.from_numpy(cu).cuda()
+    ws_f = torch.empty(max(16, B.dualkv_groups_workspace_bytes(shp, 2, P, B.OP_FWD)), dtype=torch.uint8, device="cuda")
+    ws_b = torch.empty(max(16, B.dualkv_groups_workspace_bytes(shp, 2, P, B.OP_BWD)), dtype=torch.uint8, device="cuda")
+    o, dq, dk, dv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    dk_c, dv_c = torch.empty_like(dg.k_c), torch.empty_like(dg.v_c)
+    lse = torch.empty((H, P + T), dtype=torch.float32, device="cuda")
+
+    def step():
+        B.dualkv_fwd_groups(shp, g_dev, None, P, q, k[:P], v[:P], k, v, cu_dev, None, o, lse, ws_f)
+        B.dualkv_bwd_groups(shp, g_dev, None, P, do, o, lse, q, k[:P], v[:P], k, v, cu_dev, None, dq, dk_c, dv_c, dk, dv,
+                            None, None, ws_b)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = _events(2)
+    e0.record()
+    for _ in range(steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / steps
+
+
 def time_ncopy(wl, steps, warmup):
     """The same kernels on the explicitly replicated N x (P + R_i) layout (ctx_len = 0)."""
     import numpy as np
@@ -443,8 +481,9 @@ def main():
 
     ms, wall_ms, stage = time_layer(dg, bufs, args.steps, args.warmup)
     # the other mode, for reference (fewer steps)
-    ms_alt = None
+    ms_alt = ms_fused = None
     if not args.no_alt:
+        ms_fused = time_fused_calls(dg, max(3, args.steps // 2), 2)
         dg_alt = B.upload(wl, B.FLAG_ACCUM_CTX_F32 if args.two_terms else 0)
         bufs_alt = runner.alloc(dg_alt, poison=False)
         ms_alt, _, _ = time_layer(dg_alt, bufs_alt, max(3, args.steps // 3), 1)
@@ -487,6 +526,7 @@ def main():
         "ctx_grad_mode": ("two bf16 terms (Call 1, Call 2), summed by the caller" if args.two_terms else
                           "fp32 joint accumulation of Call 1 + Call 2, one cast (Eq. 6 inside the timed step)"),
         ("ms_per_step_joint_fp32" if args.two_terms else "ms_per_step_two_terms"): (round(ms_alt, 4) if ms_alt else None),
+        "ms_per_step_fused_calls": (round(ms_fused, 4) if ms_fused else None),
         "roofline": roofline,
         "ncopy_flop_ratio": round(fl["ncopy"] / fl["layer"], 3),   # FLOPs of N-copy attention over this layer's
     }

@@ -248,3 +248,52 @@ def test_large_groups_take_the_unsplit_prompt_tile_path():
     PU.compare_lse("LSE_d", np.array(got_l), np.array(ref_l), rep)
     PU.compare("dQ_d", np.array(got_q), np.array(ref_q), rep)
     print("\n  " + "\n  ".join(rep), flush=True)
+
+
+@pytest.mark.parametrize("d,window", [(128, 0), (64, 50), (256, 0)])
+def test_call1_and_call2_in_one_launch(d, window):
+    """The prompt itself as a group of its own (a plain causal sequence, P_g = 0) next to the group of its N responses,
+    prompt and response rows in one packed buffer: one forward launch and one backward call then cover Call 1 and
+    Call 2 (Eq. 3 and Eq. 4 together).  Every output equals that of the four separate entry points: bit for bit where
+    no atomics are involved, the Call-2 shared-prompt term (fp32 atomics on these small shapes) within the parity
+    tolerance; total dK_c = Call-1 rows of dK_d + Call-2 dK_c (Eq. 6)."""
+    import torch
+    from paper_2605_15422_amd import binding as B, runner
+    print("case fused calls", d, window, flush=True)
+    H, Hk, P, lens = 8, 2, 333, [190, 0, 77, 260]
+    shape = W.Shape("fused", len(lens), P, 0, 0, H, Hk, d, window, seed=8800 + d)
+    wl = W.make_workload(shape, resp_lens=np.asarray(lens))
+    dg = B.upload(wl)
+    ref = runner.alloc(dg)
+    runner.layer_step(dg, ref)
+    N, T = len(lens), wl.total_resp
+    cat = lambda a, b: torch.cat([a, b], dim=0)
+    q, k, v, do = cat(dg.q_c, dg.q_d), cat(dg.k_c, dg.k_d), cat(dg.v_c, dg.v_d), cat(dg.do_c, dg.do_d)
+    cu = np.concatenate([[0], P + wl.cu_seqlens.astype(np.int64)]).astype(np.int32)
+    table = np.asarray([(0, 0, 0, 1), (0, P, 1, N + 1)], dtype=np.int32)
+    shp = B.make_shape(N + 1, P, P + T, int(np.diff(cu).max()), H, Hk, d, window, wl.scale, 0)
+    g_dev, cu_dev = torch.from_numpy(table).cuda(), torch.from_numpy(cu).cuda()
+    ws = lambda op: torch.full((max(16, B.dualkv_groups_workspace_bytes(shp, 2, P, op)),), 0xFF, dtype=torch.uint8, device="cuda")
+
+    def nan_like(t):
+        x = torch.empty_like(t)
+        x.view(torch.int16).fill_(0x7FC0)
+        return x
+
+    o, dq, dk, dv = nan_like(q), nan_like(q), nan_like(k), nan_like(v)
+    dk_c, dv_c = nan_like(dg.k_c), nan_like(dg.v_c)
+    lse = torch.full((H, P + T), float("nan"), device="cuda")
+    B.dualkv_fwd_groups(shp, g_dev, table, P, q, k[:P], v[:P], k, v, cu_dev, cu, o, lse, ws(B.OP_FWD))
+    B.dualkv_bwd_groups(shp, g_dev, table, P, do, o, lse, q, k[:P], v[:P], k, v, cu_dev, cu, dq, dk_c, dv_c, dk, dv,
+                        None, None, ws(B.OP_BWD))
+    torch.cuda.synchronize()
+    bits = lambda t: t.contiguous().view(torch.int16)
+    for got, want, name in ((o[:P], ref.o_c, "O_c"), (o[P:], ref.o_d, "O_d"), (dq[:P], ref.dq_c, "dQ_c"),
+                            (dq[P:], ref.dq_d, "dQ_d"), (dk[P:], ref.dk_d, "dK_d"), (dv[P:], ref.dv_d, "dV_d"),
+                            (dk[:P], ref.dk_c1, "dK_c(1)"), (dv[:P], ref.dv_c1, "dV_c(1)")):
+        assert torch.equal(bits(got), bits(want)), name
+    assert torch.equal(lse[:, :P], ref.lse_c) and torch.equal(lse[:, P:], ref.lse_d)
+    for got, want, name in ((dk_c, ref.dk_c2, "dK_c(2)"), (dv_c, ref.dv_c2, "dV_c(2)")):
+        a, c = got.float(), want.float()
+        assert bool(((a - c).abs() <= 2e-2 + 2.0 ** -8 * c.abs()).all()), name
+        assert float((a - c).norm()) <= 1e-2 * float(c.norm()), name
