@@ -13,7 +13,8 @@ hipError_t launch_dkdv(const AttnParams& p, int head_dim, hipStream_t st);
 // tuned backward kernels for head dims 64 / 128
 hipError_t launch_dq2(const AttnParams& p, int head_dim, hipStream_t st);
 hipError_t launch_dkdv4(const AttnParams& p, int head_dim, hipStream_t st);
-// tuned backward kernels for head dim 256 (dQ: 128 rows per workgroup; dK/dV: 64-key tile)
+// tuned kernels for head dim 256 (forward, dQ: 128 rows per workgroup; dK/dV: 64-key tile)
+hipError_t launch_fwd256(const AttnParams& p, hipStream_t st);
 hipError_t launch_dq256(const AttnParams& p, hipStream_t st);
 hipError_t launch_dkdv256(const AttnParams& p, hipStream_t st);
 // key tile (rows of K/V owned by one workgroup) of the dK/dV kernel for a head dim
