@@ -40,6 +40,7 @@ __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
 
 constexpr int D = 256;
 constexpr int BN = 64, HB = 32, NKS = BN / 32;   // keys per workgroup, query rows per block, key subtiles
+static_assert(NKS == 2, "the header store selects between two subtiles");
 constexpr int KS = D / 32;                       // k-steps of the 16x16x32 MFMA
 constexpr int RB = 2 * D, CPR = D / 8;
 constexpr int HT_BYTES = HB * RB;                // one Q or dO row block
@@ -84,6 +85,11 @@ __global__ __launch_bounds__(512) void dkdv256_kernel(const AttnParams p) {
     // accumulator: column l16, register r <-> row 4 g + r.
     const int kvs = wave & 1, rh = wave >> 1;
     const int l16 = lane & 15, g = lane >> 4;
+    // Which eight contraction indices of a k-step lane group g supplies is free as long as both operands agree:
+    // group g takes chunk cg = (0, 3, 1, 2)[g] of the 64-byte k-step.  A 16-byte LDS read is served in groups of
+    // sixteen lanes that are not contiguous (lanes 0-3, 12-15, 20-23, 24-27 form the first one); with cg = g the
+    // fragment reads below collide two ways in every group, with this assignment they do not.
+    const int cg = (0x9C >> (2 * g)) & 3;
     const float c = p.scale_log2;
     const int my_key[2] = {key0 + kvs * 32 + l16, key0 + kvs * 32 + 16 + l16};
     const u16 *kbase, *vbase;
@@ -103,8 +109,8 @@ __global__ __launch_bounds__(512) void dkdv256_kernel(const AttnParams p) {
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
       const int kr = min(my_key[h], region_len - 1);   // clamp: gradients of padded keys are never stored
-      const u16* kp = kbase + (int64_t)kr * kts + g * 8;
-      const u16* vp = vbase + (int64_t)kr * vts + g * 8;
+      const u16* kp = kbase + (int64_t)kr * kts + cg * 8;
+      const u16* vp = vbase + (int64_t)kr * vts + cg * 8;
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
         kf[ks][h] = *reinterpret_cast<const bf16x8*>(kp + ks * 32);
@@ -121,13 +127,13 @@ __global__ __launch_bounds__(512) void dkdv256_kernel(const AttnParams p) {
     for (int ks = 0; ks < KS; ++ks)
       asm volatile("" : : "v"(kf[ks][0]), "v"(kf[ks][1]), "v"(vfn[ks][0]), "v"(vfn[ks][1]));
 
-    // Q / dO fragment of k-step ks: row rh*16 + l16, chunk 4 ks + g.  With the tile swizzle (low two row bits
+    // Q / dO fragment of k-step ks: row rh*16 + l16, chunk 4 ks + cg.  With the tile swizzle (low two row bits
     // into chunk bits 2-3, row bits 2-3 into chunk bits 0-1) the chunk position is
-    // 4 ((ks % 4) ^ (row % 4)) + (g ^ (row / 4 % 4)) + 16 (ks / 4): four base registers serve all eight k-steps.
+    // 4 ((ks % 4) ^ (row % 4)) + (cg ^ (row / 4 % 4)) + 16 (ks / 4): four base registers serve all eight k-steps.
     const int frow = rh * 16 + l16;
     const unsigned char* fr_lo[4];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) fr_lo[j] = smem + frow * RB + 64 * (j ^ (frow & 3)) + 16 * (g ^ ((frow >> 2) & 3));
+    for (int j = 0; j < 4; ++j) fr_lo[j] = smem + frow * RB + 64 * (j ^ (frow & 3)) + 16 * (cg ^ ((frow >> 2) & 3));
     const unsigned char* fr_hi[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) fr_hi[j] = fr_lo[j] + HALF;
@@ -285,7 +291,7 @@ __global__ __launch_bounds__(512) void dkdv256_kernel(const AttnParams p) {
 #pragma unroll
     for (int t = 0; t < IPB; ++t) {
       const int tt = t % (IPB / 2);
-      voff_full[t] = LOCAL ? 0u : (uint32_t)((ld_row0 + tt * 4 * RPI) * (t < IPB / 2 ? q_ts : do_ts) * 2 + (ld_coff ^ ((tt & 1) * 32)));
+      voff_full[t] = (uint32_t)((ld_row0 + tt * 4 * RPI) * (t < IPB / 2 ? q_ts : do_ts) * 2 + (ld_coff ^ ((tt & 1) * 32)));
     }
     // row statistics: lanes 0-31 fetch LSE*log2e, lanes 32-63 fetch D; both arrays live in one workspace, D
     // first and LSE*log2e less than 4 GB behind it (checked by the launcher), so one scalar base plus an
@@ -300,7 +306,10 @@ __global__ __launch_bounds__(512) void dkdv256_kernel(const AttnParams p) {
     const u16 *q_row = nullptr, *do_row = nullptr, *q_cur = nullptr, *do_cur = nullptr;
     int64_t st_row = 0, st_cur = 0;
     bool more = false;
-    uint32_t gflags = 0;   // wave 4, lanes 0 .. NKS-1: flags of key subtile `lane` for the current row group
+    uint32_t gflags[NKS] = {};   // wave 4: flags of the key subtiles for the current row group
+    // (formed per subtile with scalar operations: comparing the schedule state with a lane-dependent key makes the
+    // compiler keep that state, and everything derived from it, in vector registers, with spills and with
+    // execution masks for the schedule's branches)
     auto enter_group = [&]() __attribute__((always_inline)) {
       row0 = rb * HB;
       nvalid = min(HB, R - row0);
@@ -309,21 +318,24 @@ __global__ __launch_bounds__(512) void dkdv256_kernel(const AttnParams p) {
       st_cur = st_row;
       g = 0;
       if (wave == 4) {
-        const int k_lo = key0 + (lane & (NKS - 1)) * 32, k_hi = k_lo + 31;
-        bool a, m;
-        if (is_ctx) {
-          a = !LOCAL || (k_hi > P + row0 - W);
-          m = LOCAL && (k_lo <= P + row0 + 31 - W);
-        } else {
-          a = k_lo <= row0 + 31;
-          m = k_hi > row0;
-          if (LOCAL) {
-            a = a && (k_hi > row0 - W);
-            m = m || (k_lo <= row0 + 31 - W);
+#pragma unroll
+        for (int i = 0; i < NKS; ++i) {
+          const int k_lo = key0 + i * 32, k_hi = k_lo + 31;
+          bool a, m;
+          if (is_ctx) {
+            a = !LOCAL || (k_hi > P + row0 - W);
+            m = LOCAL && (k_lo <= P + row0 + 31 - W);
+          } else {
+            a = k_lo <= row0 + 31;
+            m = k_hi > row0;
+            if (LOCAL) {
+              a = a && (k_hi > row0 - W);
+              m = m || (k_lo <= row0 + 31 - W);
+            }
           }
+          m = m || nvalid < HB;
+          gflags[i] = HDR_VALID | (a ? HDR_ACTIVE : 0) | (m ? HDR_MASK : 0);
         }
-        m = m || nvalid < HB;
-        gflags = HDR_VALID | (a ? HDR_ACTIVE : 0) | (m ? HDR_MASK : 0);
       }
     };
     auto init_seq = [&]() __attribute__((always_inline)) {
@@ -371,7 +383,7 @@ __global__ __launch_bounds__(512) void dkdv256_kernel(const AttnParams p) {
       constexpr int IS = decltype(ISc)::value;
       if (wave == 4 && lane < NKS) {
         u32x4 h;
-        h.x = more ? gflags : 0u;
+        h.x = more ? (lane == 0 ? gflags[0] : gflags[1]) : 0u;
         h.y = (uint32_t)row0;
         h.z = (uint32_t)nvalid;
         h.w = 0u;
@@ -383,7 +395,7 @@ __global__ __launch_bounds__(512) void dkdv256_kernel(const AttnParams p) {
         const u16* q_base = uniform_ptr(q_cur);
         const u16* do_base = uniform_ptr(do_cur);
         // (one branch for the whole block, not one per load)
-        if (__builtin_expect(!LOCAL && nvalid == HB, 1)) {
+        if (__builtin_expect(nvalid == HB, 1)) {
 #pragma unroll
           for (int t = 0; t < IPB; ++t)
             dma16(t < IPB / 2 ? q_base : do_base, voff_full[t],

@@ -10,7 +10,7 @@ import sys
 
 
 def _name(r):
-    return r["Kernel_Name"].split("(")[0].replace("void ", "")
+    return r["Kernel_Name"].replace("(anonymous namespace)::", "").split("(")[0].replace("void ", "")
 
 
 def kernel_trace(d):

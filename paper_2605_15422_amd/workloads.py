@@ -83,6 +83,7 @@ CONFIGS: Dict[str, Shape] = {
     "dim_d64":  Shape("dim_d64", 8, 16384, 2048, 2048, 32, 8, 64, 0, 1301),
     "dim_d96":  Shape("dim_d96", 8, 16384, 2048, 2048, 16, 4, 96, 0, 1302),
     "dim_d192": Shape("dim_d192", 8, 16384, 2048, 2048, 12, 4, 192, 0, 1303),
+    "dim_d256": Shape("dim_d256", 8, 16384, 2048, 2048, 16, 4, 256, 0, 1304),
     # shrunk replicas
     "cfg2_small":  Shape("cfg2_small", 4, 517, 131, 131, 8, 2, 128, 0, 2002),
     "cfg3_small":  Shape("cfg3_small", 6, 509, 17, 260, 8, 2, 128, 0, 2003),
