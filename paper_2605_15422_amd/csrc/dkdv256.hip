@@ -79,6 +79,20 @@ __global__ __launch_bounds__(512) void dkdv256_kernel(const AttnParams p) {
     region_len = p.cu ? (p.cu[seq_lo + 1] - key_row_begin) : p.total;
   }
 
+  if (LOCAL && is_ctx && min(P, key0 + BN) - 1 + W - P <= 0) {
+    // With a window only the last W prompt keys are visible to response rows: the other prompt tiles (most of them)
+    // have no row block at all.  Their gradient is zero: nothing to add to fp32 accumulators, zeros to write otherwise.
+    if (p.dkc_acc == nullptr) {
+      const int nkeys = min(P, key0 + BN) - key0;
+      for (int i = tid; i < nkeys * D; i += 512) {
+        const int key = key0 + i / D, col = i % D;
+        p.dkc.ptr[(int64_t)(key_row_begin + key) * p.dkc.ts + (int64_t)hk * p.dkc.hs + col] = 0;
+        p.dvc.ptr[(int64_t)(key_row_begin + key) * p.dvc.ts + (int64_t)hk * p.dvc.hs + col] = 0;
+      }
+    }
+    return;
+  }
+
   if (wave < 4) {
     // ================================= producer ==============================================
     // 16x16x32 operands: lane = (l16, g): A row / B column l16, contraction indices 8 g .. 8 g + 7 of the k-step;
@@ -302,7 +316,10 @@ __global__ __launch_bounds__(512) void dkdv256_kernel(const AttnParams p) {
     // ---- row-block schedule (Alg. 1, "Q-row blocks in causal support of K_n"): sequences of the tile, row
     // blocks of 32 that see at least one key of the tile, query heads of the group innermost.  All state is
     // wave-uniform and advanced incrementally.
-    int seq = seq_lo, rb = 0, rb_end = 0, g = 0, R = 0, row_begin = 0, row0 = 0, nvalid = 0;
+    // With a window the order is sequences, heads, row blocks: neighbouring key tiles then read a given (head, row
+    // block) two intervals apart instead of 2 G, close enough for the second one to find it in the L2 (a tile reads
+    // only the W + BN rows behind its keys, and without that reuse every tile fetches them from memory again).
+    int seq = seq_lo, rb = 0, rb_lo = 0, rb_end = 0, g = 0, R = 0, row_begin = 0, row0 = 0, nvalid = 0;
     const u16 *q_row = nullptr, *do_row = nullptr, *q_cur = nullptr, *do_cur = nullptr;
     int64_t st_row = 0, st_cur = 0;
     bool more = false;
@@ -313,10 +330,12 @@ __global__ __launch_bounds__(512) void dkdv256_kernel(const AttnParams p) {
     auto enter_group = [&]() __attribute__((always_inline)) {
       row0 = rb * HB;
       nvalid = min(HB, R - row0);
-      q_cur = q_row;
-      do_cur = do_row;
-      st_cur = st_row;
-      g = 0;
+      if (!LOCAL) {
+        q_cur = q_row;
+        do_cur = do_row;
+        st_cur = st_row;
+        g = 0;
+      }
       if (wave == 4) {
 #pragma unroll
         for (int i = 0; i < NKS; ++i) {
@@ -358,6 +377,13 @@ __global__ __launch_bounds__(512) void dkdv256_kernel(const AttnParams p) {
       q_row = uniform_ptr(p.q.ptr + grow * q_ts + (int64_t)hk * G * q_hs);
       do_row = uniform_ptr(p.dout.ptr + grow * do_ts + (int64_t)hk * G * do_hs);
       st_row = (int64_t)hk * G * total + grow;
+      if (LOCAL) {
+        rb_lo = rb;
+        g = 0;
+        q_cur = q_row;
+        do_cur = do_row;
+        st_cur = st_row;
+      }
     };
     auto next_group = [&]() __attribute__((always_inline)) {
       if (++rb < rb_end) {
@@ -415,12 +441,33 @@ __global__ __launch_bounds__(512) void dkdv256_kernel(const AttnParams p) {
           dma4(uniform_ptr(reinterpret_cast<const u16*>(stat_ptr + st_cur)), stat_lane_off + (uint32_t)min(l32, last) * 4u,
                smem_addr + IS * STAGE_BYTES + STAT_OFF);
         }
-        if (__builtin_expect(++g < G, 1)) {
-          q_cur += q_hs;
-          do_cur += do_hs;
-          st_cur += total;
+        if constexpr (LOCAL) {
+          if (__builtin_expect(++rb < rb_end, 1)) {
+            q_cur += (int64_t)HB * q_ts;
+            do_cur += (int64_t)HB * do_ts;
+            st_cur += HB;
+            enter_group();
+          } else if (++g < G) {
+            rb = rb_lo;
+            q_row += q_hs;
+            do_row += do_hs;
+            st_row += total;
+            q_cur = q_row;
+            do_cur = do_row;
+            st_cur = st_row;
+            enter_group();
+          } else {
+            rb = rb_end - 1;   // (next_group steps past the last row block: on to the next sequence)
+            next_group();
+          }
         } else {
-          next_group();
+          if (__builtin_expect(++g < G, 1)) {
+            q_cur += q_hs;
+            do_cur += do_hs;
+            st_cur += total;
+          } else {
+            next_group();
+          }
         }
       }
     };

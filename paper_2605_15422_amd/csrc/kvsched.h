@@ -47,6 +47,15 @@ __device__ __forceinline__ bool decode_kvblock(const AttnParams& p, int BN, KVBl
     return true;
   }
   bid -= ctx_blocks;
+  if (p.window > 0) {
+    // Workgroups go to the eight XCDs round-robin by index, each XCD with an L2 of its own.  With a window a response
+    // tile reads only the W + BN rows behind its keys, rows that its neighbours read as well: neighbouring tiles are
+    // therefore given to the same XCD (block i takes tile (i % 8) * n / 8 + i / 8), where one fetch from memory then
+    // serves many of them.  All tiles carry about the same work here, so the XCDs stay balanced; without a window the
+    // work falls with the key index and the round-robin order is the balanced one.
+    const int chunk = ((int)gridDim.x - ctx_blocks) / 8;
+    if (bid < chunk * 8) bid = (bid % 8) * chunk + bid / 8;
+  }
   b.is_ctx = false;
   b.hk = bid % p.Hk;
   const int t = bid / p.Hk;
