@@ -158,6 +158,7 @@ hipError_t run_dq(const AttnParams& p, int d, hipStream_t st) {
 hipError_t run_dkdv(const AttnParams& p, int d, hipStream_t st) {
   if (d == 64 || d == 128) return dkv::launch_dkdv4(p, d, st);
   if (d == 256) return dkv::launch_dkdv256(p, st);
+  if (d == 512) return dkv::launch_dkdv512(p, st);
   return dkv::launch_dkdv(p, d, st);
 }
 

@@ -1,4 +1,4 @@
-// Un-padded, XOR-swizzled LDS tiles for head dims 64 / 128 / 256 and the LDS transpose read.
+// Un-padded, XOR-swizzled LDS tiles for head dims 64 / 128 / 256 / 512 and the LDS transpose read.
 //
 // A tile is ROWS x D bf16, row-major, 2*D bytes per row, made of 16-byte chunks.  Chunk c of row r is
 // stored at chunk position c ^ swz<D>(r).  The swizzle makes all three access patterns used by the
@@ -25,8 +25,9 @@ typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
 template <int D>
 __device__ __forceinline__ int swz(int row) {
-  static_assert(D == 64 || D == 128 || D == 256, "swizzle defined for 64 / 128 / 256");
-  // (a 512-byte row of head dim 256 spans two bank lines: bit 4 of the chunk index does not select a bank)
+  static_assert(D == 64 || D == 128 || D == 256 || D == 512, "swizzle defined for 64 / 128 / 256 / 512");
+  // (the 512- and 1024-byte rows of head dims 256 and 512 span several bank lines: the chunk index bits from 4 on
+  // do not select a bank)
   if (D >= 128) return ((row & 3) << 2) | ((row >> 2) & 3);
   return (((row >> 1) & 1) << 2) | ((row >> 2) & 3);
 }
