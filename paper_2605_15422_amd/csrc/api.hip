@@ -153,6 +153,7 @@ hipError_t run_fwd(const AttnParams& p, int d, hipStream_t st) {
 hipError_t run_dq(const AttnParams& p, int d, hipStream_t st) {
   if (d == 64 || d == 128) return dkv::launch_dq2(p, d, st);
   if (d == 256) return dkv::launch_dq256(p, st);
+  if (d == 512) return dkv::launch_dq512(p, st);
   return dkv::launch_dq(p, d, st);
 }
 hipError_t run_dkdv(const AttnParams& p, int d, hipStream_t st) {
