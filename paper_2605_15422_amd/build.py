@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdualkv.so")
-SOURCES = ["api.hip", "qstat.hip", "fwd2.hip", "dq2.hip", "dkdv4.hip", "fwd256.hip", "dq256.hip", "dkdv256.hip", "dkdv512.hip", "dq512.hip", "kvstat.hip", "aux.hip"]
+SOURCES = ["api.hip", "qstat.hip", "fwd2.hip", "dq2.hip", "dkdv4.hip", "fwd256.hip", "dq256.hip", "dkdv256.hip", "dkdv512.hip", "dq512.hip", "fwd512.hip", "kvstat.hip", "aux.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-munsafe-fp-atomics",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument", "-Wno-inline-asm"]
 

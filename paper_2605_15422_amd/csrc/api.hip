@@ -148,6 +148,7 @@ int hip_rc(hipError_t e) { return e == hipSuccess ? DUALKV_OK : DUALKV_E_HIP; }
 hipError_t run_fwd(const AttnParams& p, int d, hipStream_t st) {
   if (d == 64 || d == 128) return dkv::launch_fwd2(p, d, st);
   if (d == 256) return dkv::launch_fwd256(p, st);
+  if (d == 512) return dkv::launch_fwd512(p, st);
   return dkv::launch_fwd(p, d, st);
 }
 hipError_t run_dq(const AttnParams& p, int d, hipStream_t st) {

@@ -21,6 +21,7 @@ hipError_t launch_dkdv256(const AttnParams& p, hipStream_t st);
 hipError_t launch_dkdv512(const AttnParams& p, hipStream_t st);
 // tuned dQ kernel for head dim 512 (64 rows per workgroup, 16-key tiles)
 hipError_t launch_dq512(const AttnParams& p, hipStream_t st);
+hipError_t launch_fwd512(const AttnParams& p, hipStream_t st);
 // key tile (rows of K/V owned by one workgroup) of the dK/dV kernel for a head dim
 int dkdv_key_tile(int head_dim);
 
