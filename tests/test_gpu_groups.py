@@ -1,6 +1,6 @@
 """Several prompt groups in ONE call of the *_groups entry points (Sec. 2.2, "multiple groups") against the fp64
 oracle evaluated group by group: heterogeneous prompt lengths (including P_g = 0), a group without sequences,
-empty responses, both gradient modes, tuned and generic kernels, with and without a window."""
+empty responses, both gradient modes, every kernel family (d = 64/128, 256, 512, 96), with and without a window."""
 import numpy as np
 import pytest
 
@@ -98,9 +98,11 @@ CASES = [
     ("d128_mixed", 8, 2, 128, 0, [(100, [40, 17, 64]), (0, [33, 5]), (257, []), (64, [1, 0, 130])]),
     ("d64_window", 4, 2, 64, 37, [(150, [120, 0]), (31, [200]), (0, [70])]),
     ("d128_many_small", 4, 4, 128, 0, [(33, [5, 9]), (1, [1]), (129, [64, 64, 64]), (200, [3]), (7, [0, 0]), (90, [31, 33])]),
-    ("d256_generic", 4, 2, 256, 0, [(130, [64, 31]), (0, [20]), (65, [])]),
-    ("d512_generic", 2, 1, 512, 0, [(65, [33, 70]), (40, [9])]),
+    ("d256_roles", 4, 2, 256, 0, [(130, [64, 31]), (0, [20]), (65, [])]),
+    ("d512_roles", 2, 1, 512, 0, [(65, [33, 70]), (40, [9])]),
     ("d96_window", 2, 2, 96, 40, [(130, [90, 33]), (50, [64])]),
+    ("d256_window", 4, 1, 256, 48, [(90, [100, 17]), (0, [70]), (200, [33, 0, 64])]),
+    ("d512_many", 4, 2, 512, 0, [(17, [16, 15]), (0, [40]), (64, []), (33, [1, 31, 17])]),
 ]
 
 

@@ -18,7 +18,7 @@ def test_config_parity(name):
     PU.full_parity(W.make_workload(W.CONFIGS[name]))
 
 
-@pytest.mark.parametrize("name", ["cfg1_tiny", "cfg3_small", "cfg5b_small"])
+@pytest.mark.parametrize("name", ["cfg1_tiny", "cfg3_small", "cfg5b_small", "cfg5a_small"])
 def test_fp32_joint_accumulation(name):
     from paper_2605_15422_amd import binding as B
     print("case accum", name, flush=True)
@@ -48,6 +48,22 @@ EDGE = [
     ("p0_r1", 1, 0, [1], 2, 2, 128, 0),
     ("many_seqs", 96, 40, [(7 * i) % 5 for i in range(96)], 4, 2, 128, 0),
     ("many_seqs_d256_win", 48, 70, [(5 * i) % 9 for i in range(48)], 2, 1, 256, 6),
+    # the producer / consumer kernels of head dims 256 and 512: row counts around their 16- and 32-row blocks, prompts
+    # around their 16-, 32- and 64-key tiles, every packing of query heads into a workgroup (G = 1, 2, 4, 8), more
+    # tiles than LDS stages, windows that end inside a tile
+    ("d256_rows", 6, 67, [15, 16, 17, 31, 33, 129], 4, 2, 256, 0),
+    ("d256_g1", 2, 129, [70, 140], 2, 2, 256, 0),
+    ("d256_g8", 2, 191, [64, 100], 8, 1, 256, 0),
+    ("d256_long", 2, 700, [300, 45], 4, 1, 256, 0),
+    ("d256_win_tile", 3, 200, [150, 64, 33], 4, 2, 256, 64),
+    ("d256_win_odd", 2, 130, [260, 90], 2, 1, 256, 97),
+    ("d256_p0", 2, 0, [130, 31], 4, 2, 256, 0),
+    ("d512_rows", 6, 35, [15, 16, 17, 31, 33, 129], 4, 2, 512, 0),
+    ("d512_g1", 2, 49, [70, 140], 2, 2, 512, 0),
+    ("d512_g8", 2, 95, [64, 100], 8, 1, 512, 0),
+    ("d512_long", 2, 400, [200, 45], 4, 2, 512, 0),
+    ("d512_p0", 2, 0, [130, 31], 2, 1, 512, 0),
+    ("d512_empty", 3, 48, [0, 20, 0], 4, 2, 512, 0),
 ]
 
 
