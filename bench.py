@@ -498,9 +498,13 @@ def main():
     }
     dom = max(kern_flops, key=lambda n: stage[n])
     achieved = kern_flops[dom] / (stage[dom] * 1e-3) / 1e12 if stage[dom] > 0 else 0.0
-    kernel_names = {"ctx_fwd": "fwd_kernel (Call 1)", "fwd": "fwd_kernel (Call 2)",
-                    "bwd_dkdv": "dkdv_kernel (Call 2)", "bwd_dq": "dq_kernel (Call 2)",
-                    "ctx_bwd_dkdv": "dkdv_kernel (Call 1)", "ctx_bwd_dq": "dq_kernel (Call 1)"}
+    # the kernel symbols that serve this head dim (as the rocprofv3 kernel trace names them)
+    fam = {64: ("fwd2_kernel", "dq2_kernel", "dkdv4_kernel"), 128: ("fwd2_kernel", "dq2_kernel", "dkdv4_kernel"),
+           256: ("fwd256_kernel", "dq256_kernel", "dkdv256_kernel"),
+           512: ("fwd512_kernel", "dq512_kernel", "dkdv512_kernel")}.get(d, ("fwd_kernel", "dq_kernel", "dkdv_kernel"))
+    kernel_names = {"ctx_fwd": fam[0] + " (Call 1)", "fwd": fam[0] + " (Call 2)",
+                    "bwd_dkdv": fam[2] + " (Call 2)", "bwd_dq": fam[1] + " (Call 2)",
+                    "ctx_bwd_dkdv": fam[2] + " (Call 1)", "ctx_bwd_dq": fam[1] + " (Call 1)"}
     roofline = {"bound": "mfma", "kernel": kernel_names[dom], "achieved": round(achieved, 2),
                 "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
                 "traffic": measured_traffic(args.config, dom), "kernel_ms": round(stage[dom], 4),

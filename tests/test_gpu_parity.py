@@ -78,8 +78,8 @@ def test_edge_cases(case):
 
 @pytest.mark.parametrize("d", [128, 96, 256, 512])
 def test_strided_views_of_one_packed_qkv_buffer(d):
-    """Zero-copy prompt/response views of one packed (T, H+2Hk, d) buffer (App. A.3 "QKV split"), through the tuned
-    (d = 128) and the generic kernels."""
+    """Zero-copy prompt/response views of one packed (T, H+2Hk, d) buffer (App. A.3 "QKV split"), through every
+    kernel family (d = 128, 96, 256, 512)."""
     import torch
     from paper_2605_15422_amd import binding as B, runner
     print("case packed_qkv", d, flush=True)
