@@ -18,6 +18,15 @@ struct QBlock {
 template <int BN>
 __device__ __forceinline__ bool decode_qblock(const AttnParams& p, QBlock& b) {
   int t = blockIdx.x;
+  if (p.window > 0) {
+    // Workgroups go to the eight XCDs round-robin by index, each XCD with an L2 of its own.  With a window a row block
+    // reads only the K / V tiles of the W keys before it, nearly the same ones as the neighbouring row blocks of its
+    // sequence: neighbours are therefore given to the same XCD (block i takes work item (i % 8) * n / 8 + i / 8).  All
+    // items carry about the same work here; without a window the work grows with the row index and the round-robin
+    // order is the balanced one.
+    const int chunk = (int)gridDim.x / 8;
+    if (t < chunk * 8) t = (t % 8) * chunk + t / 8;
+  }
   b.hk = t % p.Hk; t /= p.Hk;
   b.hc = t % p.HC; t /= p.HC;
   b.mb = p.MB - 1 - (t % p.MB);   // late (long-horizon) row blocks first
