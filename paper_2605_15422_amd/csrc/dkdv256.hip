@@ -422,24 +422,25 @@ __global__ __launch_bounds__(512) void dkdv256_kernel(const AttnParams p) {
         const u16* do_base = uniform_ptr(do_cur);
         // (one branch for the whole block, not one per load)
         if (__builtin_expect(nvalid == HB, 1)) {
-#pragma unroll
-          for (int t = 0; t < IPB; ++t)
-            dma16(t < IPB / 2 ? q_base : do_base, voff_full[t],
-                  ld_lds + (IS * STAGE_BYTES + (t < IPB / 2 ? 0 : HT_BYTES) + (t % (IPB / 2)) * 4096));
+          static_for<IPB>([&](auto Tc) __attribute__((always_inline)) {
+            constexpr int t = decltype(Tc)::value;
+            dma16_at<IS * STAGE_BYTES + (t < IPB / 2 ? 0 : HT_BYTES) + (t % (IPB / 2)) * 4096>(
+                t < IPB / 2 ? q_base : do_base, voff_full[t], ld_lds);
+          });
         } else {
-#pragma unroll
-          for (int t = 0; t < IPB; ++t) {
-            const bool is_q = t < IPB / 2;
-            const int tt = t % (IPB / 2);
+          static_for<IPB>([&](auto Tc) __attribute__((always_inline)) {
+            constexpr int t = decltype(Tc)::value;
+            constexpr bool is_q = t < IPB / 2;
+            constexpr int tt = t % (IPB / 2);
             const int row = ld_row0 + tt * 4 * RPI;
             const uint32_t voff = __umul24((unsigned)min(row, last), (unsigned)((is_q ? q_ts : do_ts) * 2)) +
                                   (uint32_t)(ld_coff ^ ((tt & 1) * 32));
-            dma16(is_q ? q_base : do_base, voff, ld_lds + (IS * STAGE_BYTES + (is_q ? 0 : HT_BYTES) + tt * 4096));
-          }
+            dma16_at<IS * STAGE_BYTES + (is_q ? 0 : HT_BYTES) + tt * 4096>(is_q ? q_base : do_base, voff, ld_lds);
+          });
         }
         if (wave == 5) {
-          dma4(uniform_ptr(reinterpret_cast<const u16*>(stat_ptr + st_cur)), stat_lane_off + (uint32_t)min(l32, last) * 4u,
-               smem_addr + IS * STAGE_BYTES + STAT_OFF);
+          dma4_at<IS * STAGE_BYTES + STAT_OFF>(uniform_ptr(reinterpret_cast<const u16*>(stat_ptr + st_cur)),
+                                               stat_lane_off + (uint32_t)min(l32, last) * 4u, smem_addr);
         }
         if constexpr (LOCAL) {
           if (__builtin_expect(++rb < rb_end, 1)) {

@@ -350,23 +350,24 @@ __global__ __launch_bounds__(512) void dkdv512_kernel(const AttnParams p) {
         const u16* do_base = uniform_ptr(do_cur);
         // (one branch for the whole block, not one per load)
         if (__builtin_expect(nvalid == HB, 1)) {
-#pragma unroll
-          for (int t = 0; t < IPB; ++t)
-            dma16(t < IPB / 2 ? q_base : do_base, voff_full[t],
-                  ld_lds + (IS * STAGE_BYTES + (t < IPB / 2 ? 0 : HT_BYTES) + (t % (IPB / 2)) * 4096));
+          static_for<IPB>([&](auto Tc) __attribute__((always_inline)) {
+            constexpr int t = decltype(Tc)::value;
+            dma16_at<IS * STAGE_BYTES + (t < IPB / 2 ? 0 : HT_BYTES) + (t % (IPB / 2)) * 4096>(
+                t < IPB / 2 ? q_base : do_base, voff_full[t], ld_lds);
+          });
         } else {
-#pragma unroll
-          for (int t = 0; t < IPB; ++t) {
-            const bool is_q = t < IPB / 2;
+          static_for<IPB>([&](auto Tc) __attribute__((always_inline)) {
+            constexpr int t = decltype(Tc)::value;
+            constexpr bool is_q = t < IPB / 2;
             const int row = jb + (t % (IPB / 2)) * 4;
             const uint32_t voff = __umul24((unsigned)min(row, last), (unsigned)((is_q ? q_ts : do_ts) * 2)) +
                                   (uint32_t)((lane ^ swz<D>(row)) * 16);
-            dma16(is_q ? q_base : do_base, voff, ld_lds + (IS * STAGE_BYTES + (is_q ? 0 : HT_BYTES) + (t % (IPB / 2)) * 4096));
-          }
+            dma16_at<IS * STAGE_BYTES + (is_q ? 0 : HT_BYTES) + (t % (IPB / 2)) * 4096>(is_q ? q_base : do_base, voff, ld_lds);
+          });
         }
         if (wave == 5) {
-          dma4(uniform_ptr(reinterpret_cast<const u16*>(stat_ptr + st_cur)), stat_lane_off + (uint32_t)min(lane & 15, last) * 4u,
-               smem_addr + IS * STAGE_BYTES + STAT_OFF);
+          dma4_at<IS * STAGE_BYTES + STAT_OFF>(uniform_ptr(reinterpret_cast<const u16*>(stat_ptr + st_cur)),
+                                               stat_lane_off + (uint32_t)min(lane & 15, last) * 4u, smem_addr);
         }
         if (__builtin_expect(++g < G, 1)) {
           q_cur += q_hs;

@@ -9,6 +9,8 @@
 // load would also wait for every tile in flight.  Loads issued before the loop are "consumed" by an empty asm
 // statement so that their wait lands before the loop.
 #pragma once
+#include <type_traits>
+#include <utility>
 #include "common.h"
 
 namespace dkv {
@@ -30,6 +32,33 @@ __device__ __forceinline__ void dma4(const void* sbase, uint32_t voff, uint32_t 
                :
                : "s"(lds_addr), "v"(voff), "s"(sbase)
                : "memory", "m0");
+}
+// The same with the LDS address given as a wave-uniform base plus a compile-time offset, added into M0 inside the
+// statement.  In a loop unrolled over LDS stages every load has a different constant address; given as one value,
+// the compiler computes all of them ahead of the loop, runs out of scalar registers and reloads each from a spill
+// slot (a vector-register lane read per load) instead of re-adding a constant.
+template <int OFF>
+__device__ __forceinline__ void dma16_at(const void* sbase, uint32_t voff, uint32_t lds_base) {
+  asm volatile("s_add_u32 m0, %0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :
+               : "s"(lds_base), "v"(voff), "s"(sbase), "n"(OFF)
+               : "memory", "m0", "scc");
+}
+template <int OFF>
+__device__ __forceinline__ void dma4_at(const void* sbase, uint32_t voff, uint32_t lds_base) {
+  asm volatile("s_add_u32 m0, %0, %3\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
+               :
+               : "s"(lds_base), "v"(voff), "s"(sbase), "n"(OFF)
+               : "memory", "m0", "scc");
+}
+// f(std::integral_constant<int, 0>{}), ..., f(std::integral_constant<int, N - 1>{}): a loop whose index is a constant expression
+template <typename F, int... I>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  static_for_impl(f, std::make_integer_sequence<int, N>{});
 }
 template <int N>
 __device__ __forceinline__ void wait_vm() {
