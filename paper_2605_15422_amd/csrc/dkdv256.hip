@@ -404,9 +404,14 @@ __global__ __launch_bounds__(512) void dkdv256_kernel(const AttnParams p) {
       }
     };
     uint32_t vbits = 0;   // bit i: block (request position - 1 - i) exists
-    // requests the next block of the schedule (or marks the end) in stage IS and advances the schedule
-    auto issue_block = [&](auto ISc) __attribute__((always_inline)) {
+    // what the loads of the block requested last need (the windowed kernel issues them one by one, see below)
+    const u16 *ib_q = nullptr, *ib_do = nullptr, *ib_stat = nullptr;
+    int ib_last = 0;
+    // requests the next block of the schedule (or marks the end) in stage IS and advances the schedule; without its
+    // loads if the caller issues them itself (issue_one)
+    auto issue_block = [&](auto ISc, auto with_loads) __attribute__((always_inline)) {
       constexpr int IS = decltype(ISc)::value;
+      constexpr bool LOADS = decltype(with_loads)::value;
       if (wave == 4 && lane < NKS) {
         u32x4 h;
         h.x = more ? (lane == 0 ? gflags[0] : gflags[1]) : 0u;
@@ -420,8 +425,15 @@ __global__ __launch_bounds__(512) void dkdv256_kernel(const AttnParams p) {
         const int last = nvalid - 1;   // rows past the end of the sequence re-read its last row
         const u16* q_base = uniform_ptr(q_cur);
         const u16* do_base = uniform_ptr(do_cur);
+        if constexpr (LOCAL) {
+          ib_last = last;
+          ib_q = q_base;
+          ib_do = do_base;
+          ib_stat = uniform_ptr(reinterpret_cast<const u16*>(stat_ptr + st_cur));
+        }
         // (one branch for the whole block, not one per load)
-        if (__builtin_expect(nvalid == HB, 1)) {
+        if constexpr (!LOADS) {
+        } else if (__builtin_expect(nvalid == HB, 1)) {
           static_for<IPB>([&](auto Tc) __attribute__((always_inline)) {
             constexpr int t = decltype(Tc)::value;
             dma16_at<IS * STAGE_BYTES + (t < IPB / 2 ? 0 : HT_BYTES) + (t % (IPB / 2)) * 4096>(
@@ -438,7 +450,7 @@ __global__ __launch_bounds__(512) void dkdv256_kernel(const AttnParams p) {
             dma16_at<IS * STAGE_BYTES + (is_q ? 0 : HT_BYTES) + tt * 4096>(is_q ? q_base : do_base, voff, ld_lds);
           });
         }
-        if (wave == 5) {
+        if (LOADS && wave == 5) {
           dma4_at<IS * STAGE_BYTES + STAT_OFF>(uniform_ptr(reinterpret_cast<const u16*>(stat_ptr + st_cur)),
                                                stat_lane_off + (uint32_t)min(l32, last) * 4u, smem_addr);
         }
@@ -472,6 +484,20 @@ __global__ __launch_bounds__(512) void dkdv256_kernel(const AttnParams p) {
         }
       }
     };
+    // Load instruction t of the block requested last, without a branch: the rows of a partial last block are clamped with
+    // three vector operations, and after the end of the schedule the loads repeat the last block's, into a stage whose
+    // header says that it holds nothing.
+    const int q_neg = -q_ts * 2, do_neg = -do_ts * 2;
+    auto issue_one = [&](auto ISc, auto Tc) __attribute__((always_inline)) {
+      constexpr int IS = decltype(ISc)::value, t = decltype(Tc)::value;
+      constexpr bool is_q = t < IPB / 2;
+      constexpr int tt = t % (IPB / 2);
+      const int over = max(ld_row0 + tt * 4 * RPI - ib_last, 0);   // rows past the last valid one step back to it
+      const uint32_t voff = (uint32_t)__mul24(over, is_q ? q_neg : do_neg) + voff_full[t];
+      dma16_at<IS * STAGE_BYTES + (is_q ? 0 : HT_BYTES) + tt * 4096>(is_q ? ib_q : ib_do, voff, ld_lds);
+      if (t == IPB - 1 && wave == 5)
+        dma4_at<IS * STAGE_BYTES + STAT_OFF>(ib_stat, stat_lane_off + (uint32_t)min(l32, ib_last) * 4u, smem_addr);
+    };
     // Block b is requested AHEAD blocks early and must have landed by the end of interval b - 2 (the
     // producer reads its operands one interval early): the youngest block (IPB loads per wave; wave 5
     // issues one more, for it the bound is a little stricter) may stay in flight.  If the newest request was
@@ -489,9 +515,29 @@ __global__ __launch_bounds__(512) void dkdv256_kernel(const AttnParams p) {
         break;
       }
     }
-    issue_block(IC<0>{});
-    issue_block(IC<1>{});
-    issue_block(IC<2>{});
+    if (LOCAL && !more) {
+      // No row block at all: the windowed main loop issues its loads unconditionally and would have no valid address.
+      // One empty header ends the producers' schedule after one interval; the gradient of these keys is zero.
+      if (wave == 4 && lane < NKS) *reinterpret_cast<u32x4*>(smem + HDR_OFF + lane * 16) = u32x4{0u, 0u, 0u, 0u};
+      __syncthreads();
+      __syncthreads();   // the producers' only interval
+      const bool to_acc = is_ctx ? (p.dkc_acc != nullptr) : (p.dkd_acc != nullptr);
+      if (!to_acc) {
+        const TViewOut& gk = is_ctx ? p.dkc : p.dkd;
+        const TViewOut& gv = is_ctx ? p.dvc : p.dvd;
+        const int nkeys = min(region_len, key0 + BN) - key0;
+        for (int i = tid - 256; i < nkeys * D; i += 256) {
+          const int64_t grow = key_row_begin + key0 + i / D;
+          const int col = i % D;
+          gk.ptr[grow * gk.ts + (int64_t)hk * gk.hs + col] = 0;
+          gv.ptr[grow * gv.ts + (int64_t)hk * gv.hs + col] = 0;
+        }
+      }
+      return;
+    }
+    issue_block(IC<0>{}, std::true_type{});
+    issue_block(IC<1>{}, std::true_type{});
+    issue_block(IC<2>{}, std::true_type{});
     wait_loads();
 
     // Each consumer wave owns the head-dim blocks jb and jb + 4 (128 columns apart: the same swizzled chunk
@@ -513,14 +559,33 @@ __global__ __launch_bounds__(512) void dkdv256_kernel(const AttnParams p) {
     const unsigned char* tr1_hi = tr1_lo + HALF;
     const unsigned char* xr_lane = smem + XCH_OFF + lane * 16;
     bf16x8 tq[2][2], tdo[2][2];   // [k-step][head-dim block]: Q^T, dO^T operands of the row block accumulated next interval
+    if constexpr (LOCAL) {
+      // The windowed loop accumulates in every interval, also in the first one, where there is no block yet: zero operands,
+      // in the registers and in the exchange buffer that the producers fill in the second interval (every consumer clears
+      // exactly the bytes it reads: no barrier needed)
+      const u32x4 z = {0u, 0u, 0u, 0u};
+#pragma unroll
+      for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+        for (int db = 0; db < 2; ++db) {
+          tq[t2][db] = __builtin_bit_cast(bf16x8, z);
+          tdo[t2][db] = __builtin_bit_cast(bf16x8, z);
+        }
+#pragma unroll
+      for (int j = 0; j < XCH_BYTES / 1024; ++j)
+        *reinterpret_cast<u32x4*>(smem + XCH_OFF + XCH_BYTES + j * 1024 + lane * 16) = z;
+    }
 
     // one interval: accumulates block h-1, reads the transposed operands of block h (stage U), requests
     // block h + AHEAD; returns false after the end of the schedule
     auto interval = [&](auto Uc) __attribute__((always_inline)) -> bool {
       constexpr int U = decltype(Uc)::value, IS = (U + AHEAD) % NBUF, XB = (U + 1) & 1;
-      // requests first: the producers' MFMAs run meanwhile, the consumers' follow them
-      issue_block(IC<IS>{});
-      if (vbits & (1u << (AHEAD + 1))) {
+      // Without a window the requests go first: the producers' MFMAs run meanwhile, the consumers' follow them.  With a
+      // window, where the schedule costs more scalar work per block, one request behind each MFMA pair measured faster
+      // (a wave waits at a load until the memory pipeline takes it, and the MFMAs run meanwhile); the MFMAs are then not
+      // conditional (a branch around them and the loads makes the compiler copy the accumulators).
+      issue_block(IC<IS>{}, std::integral_constant<bool, !LOCAL>{});
+      if (LOCAL || (vbits & (1u << (AHEAD + 1)))) {
         const unsigned char* xr = xr_lane + XB * XCH_BYTES;
         // all P / -dS operands are requested before the first MFMA
         bf16x8 pa[2][NKS], dsa[2][NKS];
@@ -532,16 +597,28 @@ __global__ __launch_bounds__(512) void dkdv256_kernel(const AttnParams p) {
             dsa[t2][i] = *reinterpret_cast<const bf16x8*>(xr + i * 4096 + (2 + t2) * 1024);
           }
         __builtin_amdgcn_sched_barrier(0);
+        if constexpr (LOCAL) {
+          static_assert(IPB == 4 * NKS, "one load instruction per MFMA pair");
+          static_for<IPB>([&](auto Nc) __attribute__((always_inline)) {
+            constexpr int n = decltype(Nc)::value, t2 = n / (2 * NKS), db = (n / NKS) % 2, i = n % NKS;
+            dv[i][db] = mfma32(pa[t2][i], tdo[t2][db], dv[i][db]);
+            dk[i][db] = mfma32(dsa[t2][i], tq[t2][db], dk[i][db]);
+            __builtin_amdgcn_sched_barrier(0);
+            issue_one(IC<IS>{}, Nc);
+            __builtin_amdgcn_sched_barrier(0);
+          });
+        } else {
 #pragma unroll
-        for (int t2 = 0; t2 < 2; ++t2)
+          for (int t2 = 0; t2 < 2; ++t2)
 #pragma unroll
-          for (int db = 0; db < 2; ++db)
+            for (int db = 0; db < 2; ++db)
 #pragma unroll
-            for (int i = 0; i < NKS; ++i) {
-              dv[i][db] = mfma32(pa[t2][i], tdo[t2][db], dv[i][db]);
-              dk[i][db] = mfma32(dsa[t2][i], tq[t2][db], dk[i][db]);
-            }
-        __builtin_amdgcn_sched_barrier(0);
+              for (int i = 0; i < NKS; ++i) {
+                dv[i][db] = mfma32(pa[t2][i], tdo[t2][db], dv[i][db]);
+                dk[i][db] = mfma32(dsa[t2][i], tq[t2][db], dk[i][db]);
+              }
+          __builtin_amdgcn_sched_barrier(0);
+        }
       }
       const bool cur = vbits & (1u << AHEAD);
       if (__builtin_expect(cur, 1)) {
