@@ -33,6 +33,8 @@ constexpr int NSTAGE = 4, STAGE_BYTES = 2 * TILE_BYTES;   // K tile | V tile
 constexpr int XCH_OFF = NSTAGE * STAGE_BYTES;
 constexpr int XCH_BYTES = NSUB * 2048;           // [subtile][k-step 0,1][lane] x 16 B
 constexpr int SMEM_BYTES = XCH_OFF + 2 * XCH_BYTES;
+constexpr int OUT_RS = RB + 16;                  // row stride of the output tile staged in LDS (rows 4 banks apart)
+static_assert(NSUB * 32 * OUT_RS <= XCH_OFF, "the output tile fits the stages");
 constexpr int IPT = TILE_BYTES / 1024 / 4;       // 1 KB load instructions per consumer wave, tile and tensor
 constexpr int RPI = 1024 / RB;                   // rows per load instruction
 
@@ -252,13 +254,12 @@ __global__ __launch_bounds__(512) void dq256_kernel(const AttnParams p) {
       __syncthreads();
     }
 
-    // ---- epilogue: lane owns a query row, register r the head-dim column crow(r) of a block
+    // ---- epilogue: lane owns a query row, register r the head-dim column crow(r) of a block.  Stored from here a
+    // row would leave in 16-byte pieces, 32 rows per instruction; the scaled tile goes through LDS instead (the stages
+    // are free now) and leaves as whole 512-byte rows, written by all eight waves.
 #pragma unroll
     for (int s = 0; s < NSUB; ++s) {
-      const int head = b.hk * p.G + b.hc * p.GP + s / p.RSH;
-      const int row = b.blk_row0 + (s % p.RSH) * 32 + l32;
-      if (row >= R) continue;
-      u16* op = p.dq.ptr + (int64_t)(b.row_begin + row) * p.dq.ts + (int64_t)head * p.dq.hs;
+      unsigned char* orow = smem + (s * 32 + l32) * OUT_RS;
 #pragma unroll
       for (int e = 0; e < 2; ++e)
 #pragma unroll
@@ -266,8 +267,23 @@ __global__ __launch_bounds__(512) void dq256_kernel(const AttnParams p) {
           u32x2 w;
           w.x = pack2_bf16(dq[s][e][r4 * 4 + 0] * p.scale, dq[s][e][r4 * 4 + 1] * p.scale);
           w.y = pack2_bf16(dq[s][e][r4 * 4 + 2] * p.scale, dq[s][e][r4 * 4 + 3] * p.scale);
-          *reinterpret_cast<u32x2*>(op + (jb + 4 * e) * 32 + r4 * 8 + hi * 4) = w;
+          *reinterpret_cast<u32x2*>(orow + ((jb + 4 * e) * 32 + r4 * 8 + hi * 4) * 2) = w;
         }
+    }
+  }
+  __syncthreads();   // the scaled tile is in LDS
+  {
+    // thread t: 16-byte piece t % 32 of tile rows t / 32, + 16, ...
+    const int piece = tid & 31;
+#pragma unroll
+    for (int i = 0; i < NSUB * 32 / 16; ++i) {
+      const int tr = i * 16 + (tid >> 5), s = tr >> 5;
+      const int head = b.hk * p.G + b.hc * p.GP + s / p.RSH;
+      const int row = b.blk_row0 + (s % p.RSH) * 32 + (tr & 31);
+      if (row >= R) continue;
+      const u32x4 w = *reinterpret_cast<const u32x4*>(smem + tr * OUT_RS + piece * 16);
+      u16* op = p.dq.ptr + (int64_t)(b.row_begin + row) * p.dq.ts + (int64_t)head * p.dq.hs;
+      *reinterpret_cast<u32x4*>(op + piece * 8) = w;
     }
   }
 }

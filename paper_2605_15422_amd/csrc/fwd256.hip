@@ -35,6 +35,8 @@ constexpr int FAC_OFF = NSUB * 2048;             // [subtile][k-step 0,1][lane] 
 constexpr int FLAG_OFF = FAC_OFF + NSUB * 128;   // [subtile][32 rows] fp32, then one flag word per subtile
 constexpr int XCH_BYTES = FLAG_OFF + 256;
 constexpr int SMEM_BYTES = XCH_OFF + 2 * XCH_BYTES;
+constexpr int OUT_RS = RB + 16;                  // row stride of the output tile staged in LDS (rows 4 banks apart)
+static_assert(NSUB * 32 * OUT_RS <= XCH_OFF, "the output tile fits the stages");
 constexpr int IPT = TILE_BYTES / 1024 / 4;       // 1 KB load instructions per consumer wave, tile and tensor
 constexpr int RPI = 1024 / RB;                   // rows per load instruction
 
@@ -277,15 +279,14 @@ __global__ __launch_bounds__(512) void fwd256_kernel(const AttnParams p) {
       __syncthreads();
     }
 
-    // ---- epilogue: lane owns a query row, register r the head-dim column crow(r) of a block
+    // ---- epilogue: lane owns a query row, register r the head-dim column crow(r) of a block.  Stored from here a
+    // row would leave in 16-byte pieces, 32 rows per instruction; the normalised tile goes through LDS instead (the
+    // stages are free now) and leaves as whole 512-byte rows, written by all eight waves.
     const unsigned char* xl = xbase + (n_tiles & 1) * XCH_BYTES;
 #pragma unroll
     for (int s = 0; s < NSUB; ++s) {
-      const int head = b.hk * p.G + b.hc * p.GP + s / p.RSH;
-      const int row = b.blk_row0 + (s % p.RSH) * 32 + l32;
-      if (row >= R) continue;
       const float inv = *reinterpret_cast<const float*>(xl + FAC_OFF + s * 128 + l32 * 4);
-      u16* op = p.out_o.ptr + (int64_t)(b.row_begin + row) * p.out_o.ts + (int64_t)head * p.out_o.hs;
+      unsigned char* orow = smem + (s * 32 + l32) * OUT_RS;
 #pragma unroll
       for (int e = 0; e < 2; ++e)
 #pragma unroll
@@ -293,8 +294,23 @@ __global__ __launch_bounds__(512) void fwd256_kernel(const AttnParams p) {
           u32x2 w;
           w.x = pack2_bf16(o[s][e][r4 * 4 + 0] * inv, o[s][e][r4 * 4 + 1] * inv);
           w.y = pack2_bf16(o[s][e][r4 * 4 + 2] * inv, o[s][e][r4 * 4 + 3] * inv);
-          *reinterpret_cast<u32x2*>(op + (jb + 4 * e) * 32 + r4 * 8 + hi * 4) = w;
+          *reinterpret_cast<u32x2*>(orow + ((jb + 4 * e) * 32 + r4 * 8 + hi * 4) * 2) = w;
         }
+    }
+  }
+  __syncthreads();   // the normalised tile is in LDS
+  {
+    // thread t: 16-byte piece t % 32 of tile rows t / 32, + 16, ...
+    const int piece = tid & 31;
+#pragma unroll
+    for (int i = 0; i < NSUB * 32 / 16; ++i) {
+      const int tr = i * 16 + (tid >> 5), s = tr >> 5;
+      const int head = b.hk * p.G + b.hc * p.GP + s / p.RSH;
+      const int row = b.blk_row0 + (s % p.RSH) * 32 + (tr & 31);
+      if (row >= R) continue;
+      const u32x4 w = *reinterpret_cast<const u32x4*>(smem + tr * OUT_RS + piece * 16);
+      u16* op = p.out_o.ptr + (int64_t)(b.row_begin + row) * p.out_o.ts + (int64_t)head * p.out_o.hs;
+      *reinterpret_cast<u32x4*>(op + piece * 8) = w;
     }
   }
 }
