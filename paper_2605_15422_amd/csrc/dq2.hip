@@ -201,17 +201,30 @@ __global__ __launch_bounds__(512) void dq2_kernel(const AttnParams p) {
     stage = stage == 2 ? 0 : stage + 1;
   }
 
-  if (row < R) {
-    u16* op = p.dq.ptr + (int64_t)(b.row_begin + row) * p.dq.ts + (int64_t)head * p.dq.hs;
+  // ---- epilogue: lane owns a query row, register r the head-dim column crow(r) of a 32-column block.  Stored from
+  // here a row would leave in 16-byte pieces, 32 rows per instruction.  The wave's scaled 32 x D tile goes through LDS
+  // instead (all stages are free after the last barrier; 16-byte chunks XOR-swizzled by the row) and is read back as
+  // whole rows.  Wave-private: no barrier.
+  unsigned char* ot = smem + wave * 32 * RB;
 #pragma unroll
-    for (int ds = 0; ds < DSUB; ++ds)
+  for (int ds = 0; ds < DSUB; ++ds)
 #pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4) {
-        u32x2 w;
-        w.x = pack2_bf16(dqacc[ds][r4 * 4 + 0] * p.scale, dqacc[ds][r4 * 4 + 1] * p.scale);
-        w.y = pack2_bf16(dqacc[ds][r4 * 4 + 2] * p.scale, dqacc[ds][r4 * 4 + 3] * p.scale);
-        *reinterpret_cast<u32x2*>(op + ds * 32 + r4 * 8 + hi * 4) = w;
-      }
+    for (int r4 = 0; r4 < 4; ++r4) {
+      u32x2 w;
+      w.x = pack2_bf16(dqacc[ds][r4 * 4 + 0] * p.scale, dqacc[ds][r4 * 4 + 1] * p.scale);
+      w.y = pack2_bf16(dqacc[ds][r4 * 4 + 2] * p.scale, dqacc[ds][r4 * 4 + 3] * p.scale);
+      *reinterpret_cast<u32x2*>(ot + l32 * RB + (((ds * 4 + r4) ^ (l32 & (CPR - 1))) << 4) + hi * 8) = w;
+    }
+  constexpr int RPS = 64 / CPR;   // rows per store instruction
+  const int chunk = lane % CPR;
+#pragma unroll
+  for (int i = 0; i < 32 / RPS; ++i) {
+    const int tr = i * RPS + lane / CPR;
+    const u32x4 w = *reinterpret_cast<const u32x4*>(ot + tr * RB + ((chunk ^ (tr & (CPR - 1))) << 4));
+    if (row0 + tr < R) {
+      u16* op = p.dq.ptr + (int64_t)(b.row_begin + row0 + tr) * p.dq.ts + (int64_t)head * p.dq.hs;
+      *reinterpret_cast<u32x4*>(op + chunk * 8) = w;
+    }
   }
 }
 

@@ -363,20 +363,33 @@ __global__ __launch_bounds__(kFwdWaves * 64) void fwd2_kernel(const AttnParams p
   // the product of the last half tile
   pv_half(smem + V_RING + ((b.n_tiles - 1) & (NSTAGE - 1)) * C::TILE_BYTES + 32 * C::RB, pB);
 
+  // ---- epilogue: lane owns a query row, register r the head-dim column crow(r) of a 32-column block.  Stored from
+  // here a row would leave in 16-byte pieces, 32 rows per instruction.  The wave's normalised 32 x D tile goes through
+  // LDS instead: its own 32 rows of the K ring (free since the last barrier: only V is read after it; 16-byte chunks
+  // XOR-swizzled by the row), read back as whole rows.  Wave-private: no barrier.
   const float l = xor32_sum(l_sum);
-  if (row < R) {
-    const float inv = 1.0f / l;
-    u16* op = p.out_o.ptr + (int64_t)(b.row_begin + row) * p.out_o.ts + (int64_t)head * p.out_o.hs;
+  const float inv = 1.0f / l;
+  unsigned char* ot = smem + wave * 32 * C::RB;
 #pragma unroll
-    for (int ds = 0; ds < C::DSUB; ++ds)
+  for (int ds = 0; ds < C::DSUB; ++ds)
 #pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4) {
-        u32x2 w;
-        w.x = pack2_bf16(oacc[ds][r4 * 4 + 0] * inv, oacc[ds][r4 * 4 + 1] * inv);
-        w.y = pack2_bf16(oacc[ds][r4 * 4 + 2] * inv, oacc[ds][r4 * 4 + 3] * inv);
-        *reinterpret_cast<u32x2*>(op + ds * 32 + r4 * 8 + hi * 4) = w;
-      }
-    if (hi == 0) p.lse[(int64_t)head * p.total + b.row_begin + row] = (m_ref + log2f(l)) * LN2;
+    for (int r4 = 0; r4 < 4; ++r4) {
+      u32x2 w;
+      w.x = pack2_bf16(oacc[ds][r4 * 4 + 0] * inv, oacc[ds][r4 * 4 + 1] * inv);
+      w.y = pack2_bf16(oacc[ds][r4 * 4 + 2] * inv, oacc[ds][r4 * 4 + 3] * inv);
+      *reinterpret_cast<u32x2*>(ot + l32 * C::RB + (((ds * 4 + r4) ^ (l32 & (C::CPR - 1))) << 4) + hi * 8) = w;
+    }
+  if (hi == 0 && row < R) p.lse[(int64_t)head * p.total + b.row_begin + row] = (m_ref + log2f(l)) * LN2;
+  constexpr int RPS = 64 / C::CPR;   // rows per store instruction
+  const int chunk = lane % C::CPR;
+#pragma unroll
+  for (int i = 0; i < 32 / RPS; ++i) {
+    const int tr = i * RPS + lane / C::CPR;
+    const u32x4 w = *reinterpret_cast<const u32x4*>(ot + tr * C::RB + ((chunk ^ (tr & (C::CPR - 1))) << 4));
+    if (row0 + tr < R) {
+      u16* op = p.out_o.ptr + (int64_t)(b.row_begin + row0 + tr) * p.out_o.ts + (int64_t)head * p.out_o.hs;
+      *reinterpret_cast<u32x4*>(op + chunk * 8) = w;
+    }
   }
 }
 
