@@ -324,6 +324,11 @@ __global__ __launch_bounds__(512) void dkdv256_kernel(const AttnParams p) {
     int64_t st_row = 0, st_cur = 0;
     bool more = false;
     uint32_t gflags[NKS] = {};   // wave 4: flags of the key subtiles for the current row group
+    // Row blocks [plain_lo, plain_hi) (first rows) of a windowed run see every key of the tile, none masked: in the response
+    // region those whose first row is at or past the tile's last key and whose last row is still inside the window of its
+    // first key; in the prompt region (every response row is past every prompt key) only the window bounds them.
+    const int plain_lo = is_ctx ? INT_MIN : key0 + BN - 1;
+    const int plain_hi = is_ctx ? key0 + W - 31 - P : key0 + W - 31;
     // (formed per subtile with scalar operations: comparing the schedule state with a lane-dependent key makes the
     // compiler keep that state, and everything derived from it, in vector registers, with spills and with
     // execution masks for the schedule's branches)
@@ -337,6 +342,12 @@ __global__ __launch_bounds__(512) void dkdv256_kernel(const AttnParams p) {
         g = 0;
       }
       if (wave == 4) {
+        // most row blocks see every key of the tile: two comparisons settle them
+        if (LOCAL && row0 >= plain_lo && row0 < plain_hi && nvalid == HB) {
+#pragma unroll
+          for (int i = 0; i < NKS; ++i) gflags[i] = HDR_VALID | HDR_ACTIVE;
+          return;
+        }
 #pragma unroll
         for (int i = 0; i < NKS; ++i) {
           const int k_lo = key0 + i * 32, k_hi = k_lo + 31;
