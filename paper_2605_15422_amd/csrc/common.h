@@ -206,4 +206,18 @@ struct AttnParams {
   int n_split;                           // ctx tiles: the sequence loop is cut in n_split parts
 };
 
+// A scalar kernel argument in scalar registers of its own.  The arguments arrive in blocks of up to sixteen registers;
+// a value used inside a loop keeps its whole block alive, and when scalar registers run short the block is spilled and
+// reloaded as a whole for it.  The copy ends the block's life here.
+__device__ __forceinline__ int own_sgpr(int v) {
+  int r;
+  asm volatile("s_mov_b32 %0, %1" : "=s"(r) : "s"(v));
+  return r;
+}
+__device__ __forceinline__ int64_t own_sgpr(int64_t v) {
+  int64_t r;
+  asm volatile("s_mov_b64 %0, %1" : "=s"(r) : "s"(v));
+  return r;
+}
+
 }  // namespace dkv

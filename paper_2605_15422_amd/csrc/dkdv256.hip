@@ -293,9 +293,14 @@ __global__ __launch_bounds__(512) void dkdv256_kernel(const AttnParams p) {
     // dO; lane l lands at LDS chunk position l % CPR of row (l / CPR) of the instruction, so it fetches the
     // chunk that the tile swizzle stores there.  The swizzle has a period of 16 rows and the instructions of a
     // wave are 8 rows apart: odd t flip bit 1 of the chunk index.
-    const int G = p.G;
-    const int q_ts = (int)p.q.ts, do_ts = (int)p.dout.ts;
-    const int64_t q_hs = p.q.hs, do_hs = p.dout.hs, total = p.total;
+    // (registers of their own for the loop's scalar inputs: measured faster without a window, slower with one)
+    auto keep = [](auto v) __attribute__((always_inline)) {
+      if constexpr (LOCAL) return v;
+      else return own_sgpr(v);
+    };
+    const int G = keep(p.G);
+    const int q_ts = keep((int)p.q.ts), do_ts = keep((int)p.dout.ts);
+    const int64_t q_hs = keep(p.q.hs), do_hs = keep(p.dout.hs), total = keep((int64_t)p.total);
     const int ld_row0 = jb * RPI + lane / CPR;
     const int ld_coff = ((lane % CPR) ^ swz<D>(ld_row0)) * 16;
     const uint32_t ld_lds = smem_addr + jb * 1024;

@@ -251,9 +251,9 @@ __global__ __launch_bounds__(512) void dkdv4_kernel(const AttnParams p) {
     // ---- global -> LDS loads: instruction i = jb + 4 t of a row block covers RPI rows of Q (t < IPB/2) or
     // dO; lane l lands at LDS chunk position l % CPR of row (l / CPR) of the instruction, so it fetches the
     // chunk that the tile swizzle stores there (the swizzle has period 4 RPI rows: one offset serves all t).
-    const int G = p.G;
-    const int q_ts = (int)p.q.ts, do_ts = (int)p.dout.ts;
-    const int64_t q_hs = p.q.hs, do_hs = p.dout.hs, total = p.total;
+    const int G = own_sgpr(p.G);
+    const int q_ts = own_sgpr((int)p.q.ts), do_ts = own_sgpr((int)p.dout.ts);
+    const int64_t q_hs = own_sgpr(p.q.hs), do_hs = own_sgpr(p.dout.hs), total = own_sgpr((int64_t)p.total);
     const int ld_row0 = jb * RPI + lane / CPR;
     const int ld_coff = ((lane % CPR) ^ swz<D>(ld_row0)) * 16;
     const uint32_t ld_lds = smem_addr + jb * 1024;

@@ -253,9 +253,9 @@ __global__ __launch_bounds__(512) void dkdv512_kernel(const AttnParams p) {
     const uint32_t smem_addr = (uint32_t)reinterpret_cast<uintptr_t>(smem);
     // ---- global -> LDS loads: one instruction per 1 KB row; this wave takes rows jb, jb + 4, jb + 8, jb + 12 of Q and
     // of dO.  Lane l lands at chunk position l of the row and fetches the chunk that the tile swizzle stores there.
-    const int G = p.G;
-    const int q_ts = (int)p.q.ts, do_ts = (int)p.dout.ts;
-    const int64_t q_hs = p.q.hs, do_hs = p.dout.hs, total = p.total;
+    const int G = own_sgpr(p.G);
+    const int q_ts = own_sgpr((int)p.q.ts), do_ts = own_sgpr((int)p.dout.ts);
+    const int64_t q_hs = own_sgpr(p.q.hs), do_hs = own_sgpr(p.dout.hs), total = own_sgpr((int64_t)p.total);
     // per-lane global offsets of this wave's load instructions for a block of 16 valid rows (a partial last
     // block clamps its rows instead: rare, computed on the spot)
     uint32_t voff_full[IPB];
