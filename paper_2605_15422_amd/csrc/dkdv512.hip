@@ -50,7 +50,7 @@ constexpr int NBUF = 4;
 constexpr int XCH_OFF = NBUF * STAGE_BYTES;
 constexpr int XCH_BYTES = 2048;                  // [P | dS][lane] x 16 B
 constexpr int SMEM_BYTES = XCH_OFF + 2 * XCH_BYTES;
-constexpr int IPB = 2 * HB / 4;                  // 1 KB load instructions (one row each) per consumer wave and block
+constexpr int IPB = HB / 4;                      // 1 KB load instructions (one row each) per wave, block and tensor
 constexpr int HALF = (NBUF / 2) * STAGE_BYTES;   // second base register of every LDS operand (16-bit offset field)
 static_assert(STAGE_BYTES + HT_BYTES + 1024 < 65536, "immediate offsets");
 
@@ -131,6 +131,59 @@ __global__ __launch_bounds__(512) void dkdv512_kernel(const AttnParams p) {
     // consumer A operand (32x32x16): lane (key, hi'), element e <-> row 4 hi' + 8 (e / 4) + e % 4 of the block.
     // This lane holds rows 4 g + r: hi' = g % 2, elements 4 (g / 2) .. + 3.
     unsigned char* xw = smem + XCH_OFF + pb * XCH_BYTES + ((g & 1) * 32 + kh * 16 + l16) * 16 + (g >> 1) * 8;
+
+    // ---- the producers request the dO rows and the row statistics of a block (the consumers its Q rows).  A CU takes one
+    // 1 KB request per ~17 cycles, and a wave waits at each request until it is taken: the 33 requests of a block keep
+    // the memory pipeline busy for about as long as the block's MFMAs keep the matrix pipes busy.  The consumers make
+    // theirs at the start of an interval, while the producers' MFMAs run, the producers after their MFMAs, while the
+    // consumers' run.  dO and the statistics are first read one interval later than Q.  In interval t: block t + 1, whose header (with the
+    // addresses) the consumers wrote in interval t - 1; this wave takes rows wave, wave + 4, ... as the consumers do for Q.
+    // Row statistics: lanes 0-15 fetch LSE*log2e, lanes 16-31 fetch D (lanes 32-63 repeat them into the unused half
+    // of the 256-byte area); both arrays live in one workspace, D first and LSE*log2e less than 4 GB behind it
+    // (checked by the launcher), so one scalar base plus an unsigned 32-bit lane offset addresses both.
+    const uint32_t smem_addr = (uint32_t)reinterpret_cast<uintptr_t>(smem);
+    const uint32_t ld_lds = smem_addr + wave * 1024;
+    const int do_neg = own_sgpr(-(int)p.dout.ts * 2);
+    uint32_t voff_do[IPB];
+#pragma unroll
+    for (int t = 0; t < IPB; ++t) {
+      const int row = wave + t * 4;
+      voff_do[t] = (uint32_t)(-row * do_neg + ((lane ^ swz<D>(row)) * 16));
+    }
+    const uint32_t stat_lane_off = (lane & 16) ? 0u : (uint32_t)((const char*)p.lse2 - (const char*)p.dvec);
+    bool issued = false;   // requests made in the current interval
+    auto request_do = [&](auto NSc) __attribute__((always_inline)) {
+      constexpr int NS = decltype(NSc)::value;
+      const u32x4 h = *reinterpret_cast<const u32x4*>(smem + NS * STAGE_BYTES + HDR_OFF);
+      const u32x4 a = *reinterpret_cast<const u32x4*>(smem + NS * STAGE_BYTES + HDR_OFF + 16);
+      if (!(__builtin_amdgcn_readfirstlane((int)h.x) & HDR_VALID)) return;
+      const int last = __builtin_amdgcn_readfirstlane((int)h.z) - 1;   // rows past the end re-read the last row
+      const u16* dob = reinterpret_cast<const u16*>(((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)a.y) << 32) |
+                                                    (uint32_t)__builtin_amdgcn_readfirstlane((int)a.x));
+      static_for<IPB>([&](auto Tc) __attribute__((always_inline)) {
+        constexpr int t = decltype(Tc)::value;
+        const int over = max(wave + t * 4 - last, 0);
+        dma16_at<NS * STAGE_BYTES + HT_BYTES + t * 4096>(dob, (uint32_t)__mul24(over, do_neg) + voff_do[t], ld_lds);
+      });
+      if (wave == 1) {
+        const u16* stp = reinterpret_cast<const u16*>(((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)a.w) << 32) |
+                                                      (uint32_t)__builtin_amdgcn_readfirstlane((int)a.z));
+        dma4_at<NS * STAGE_BYTES + STAT_OFF>(stp, stat_lane_off + (uint32_t)min(lane & 15, last) * 4u, smem_addr);
+      }
+      issued = true;
+    };
+    // end of an interval: the requests of the interval before this one have landed (in the next interval their first
+    // readers start), this interval's may stay in flight
+    auto end_interval = [&]() __attribute__((always_inline)) {
+      if (__builtin_expect(issued, 1)) {
+        if (wave == 1) wait_vm<IPB + 1>();
+        else wait_vm<IPB>();
+      } else {
+        wait_vm<0>();
+      }
+      issued = false;
+      __syncthreads();
+    };
 
     int flags = 0, row0 = 0, nvalid = 0;
     f32x4 s = {0.f, 0.f, 0.f, 0.f};   // scores of the block in flight, times scale * log2(e)
@@ -222,15 +275,26 @@ __global__ __launch_bounds__(512) void dkdv512_kernel(const AttnParams p) {
     // the following interval.  `left` counts down the intervals after the end mark.
     int left = 0;
     auto first = [&](auto Uc) __attribute__((always_inline)) -> bool {   // interval of an S phase; false: stop
-      if (left == 0) left = s_phase(Uc);
-      __syncthreads();
+      constexpr int U = decltype(Uc)::value;
+      if (left == 0) {
+        left = s_phase(Uc);
+        if (left == 0) request_do(IC<(U + 1) % NBUF>{});
+      }
+      end_interval();
       return left == 0 || --left > 0;
     };
     auto second = [&](auto Uc) __attribute__((always_inline)) -> bool {   // interval of a dP phase (block in stage U)
-      if (left == 0) dp_phase(Uc);
-      __syncthreads();
+      constexpr int U = decltype(Uc)::value;
+      if (left == 0) {
+        dp_phase(Uc);
+        request_do(IC<(U + 2) % NBUF>{});
+      }
+      end_interval();
       return left == 0 || --left > 0;
     };
+    // (interval 0 requests blocks 0 and 1; `issued` stands for block 1 alone: block 0 must land in this interval)
+    request_do(IC<0>{});
+    issued = false;
     if (pb == 0) {
       while (true) {
         if (!first(IC<0>{})) break;
@@ -261,15 +325,11 @@ __global__ __launch_bounds__(512) void dkdv512_kernel(const AttnParams p) {
     uint32_t voff_full[IPB];
 #pragma unroll
     for (int t = 0; t < IPB; ++t) {
-      const int row = jb + (t % (IPB / 2)) * 4;
-      voff_full[t] = (uint32_t)(row * (t < IPB / 2 ? q_ts : do_ts) * 2 + ((lane ^ swz<D>(row)) * 16));
+      const int row = jb + t * 4;
+      voff_full[t] = (uint32_t)(row * q_ts * 2 + ((lane ^ swz<D>(row)) * 16));
     }
     const uint32_t ld_lds = smem_addr + jb * 1024;
-    // row statistics: lanes 0-15 fetch LSE*log2e, lanes 16-31 fetch D (lanes 32-63 repeat them into the unused half
-    // of the 256-byte area); both arrays live in one workspace, D first and LSE*log2e less than 4 GB behind it
-    // (checked by the launcher), so one scalar base plus an unsigned 32-bit lane offset addresses both
     const float* stat_ptr = p.dvec;
-    const uint32_t stat_lane_off = (lane & 16) ? 0u : (uint32_t)((const char*)p.lse2 - (const char*)p.dvec);
 
     // ---- row-block schedule (Alg. 1, "Q-row blocks in causal support of K_n"): sequences of the tile, row
     // blocks of 16 that see at least one key of the tile, query heads of the group innermost.  All state is
@@ -335,39 +395,33 @@ __global__ __launch_bounds__(512) void dkdv512_kernel(const AttnParams p) {
     auto issue_block = [&](auto ISc) __attribute__((always_inline)) {
       constexpr int IS = decltype(ISc)::value;
       if (!more) ++ends;
-      if (wave == 4 && lane == 0) {
+      if (wave == 4 && lane < 2) {
+        // lane 0: the block's header; lane 1: where its dO rows and row statistics are (the producers request those)
+        const uint64_t dop = reinterpret_cast<uint64_t>(do_cur), stp = reinterpret_cast<uint64_t>(stat_ptr + st_cur);
         u32x4 h;
-        h.x = more ? gflags : 0u;
-        h.y = (uint32_t)row0;
-        h.z = (uint32_t)nvalid;
-        h.w = ends;
-        *reinterpret_cast<u32x4*>(smem + IS * STAGE_BYTES + HDR_OFF) = h;
+        h.x = lane == 0 ? (more ? gflags : 0u) : (uint32_t)dop;
+        h.y = lane == 0 ? (uint32_t)row0 : (uint32_t)(dop >> 32);
+        h.z = lane == 0 ? (uint32_t)nvalid : (uint32_t)stp;
+        h.w = lane == 0 ? ends : (uint32_t)(stp >> 32);
+        *reinterpret_cast<u32x4*>(smem + IS * STAGE_BYTES + HDR_OFF + lane * 16) = h;
       }
       vbits = (vbits << 1) | (more ? 1u : 0u);
       if (__builtin_expect(more, 1)) {
         const int last = nvalid - 1;   // rows past the end of the sequence re-read its last row
         const u16* q_base = uniform_ptr(q_cur);
-        const u16* do_base = uniform_ptr(do_cur);
         // (one branch for the whole block, not one per load)
         if (__builtin_expect(nvalid == HB, 1)) {
           static_for<IPB>([&](auto Tc) __attribute__((always_inline)) {
             constexpr int t = decltype(Tc)::value;
-            dma16_at<IS * STAGE_BYTES + (t < IPB / 2 ? 0 : HT_BYTES) + (t % (IPB / 2)) * 4096>(
-                t < IPB / 2 ? q_base : do_base, voff_full[t], ld_lds);
+            dma16_at<IS * STAGE_BYTES + t * 4096>(q_base, voff_full[t], ld_lds);
           });
         } else {
           static_for<IPB>([&](auto Tc) __attribute__((always_inline)) {
             constexpr int t = decltype(Tc)::value;
-            constexpr bool is_q = t < IPB / 2;
-            const int row = jb + (t % (IPB / 2)) * 4;
-            const uint32_t voff = __umul24((unsigned)min(row, last), (unsigned)((is_q ? q_ts : do_ts) * 2)) +
-                                  (uint32_t)((lane ^ swz<D>(row)) * 16);
-            dma16_at<IS * STAGE_BYTES + (is_q ? 0 : HT_BYTES) + (t % (IPB / 2)) * 4096>(is_q ? q_base : do_base, voff, ld_lds);
+            const int row = jb + t * 4;
+            const uint32_t voff = __umul24((unsigned)min(row, last), (unsigned)(q_ts * 2)) + (uint32_t)((lane ^ swz<D>(row)) * 16);
+            dma16_at<IS * STAGE_BYTES + t * 4096>(q_base, voff, ld_lds);
           });
-        }
-        if (wave == 5) {
-          dma4_at<IS * STAGE_BYTES + STAT_OFF>(uniform_ptr(reinterpret_cast<const u16*>(stat_ptr + st_cur)),
-                                               stat_lane_off + (uint32_t)min(lane & 15, last) * 4u, smem_addr);
         }
         if (__builtin_expect(++g < G, 1)) {
           q_cur += q_hs;
