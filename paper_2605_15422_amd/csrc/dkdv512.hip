@@ -14,10 +14,10 @@
 //
 //   * producers (waves 0-3): Q / dO fragments are read from LDS as they are needed; P and -dS leave as bf16
 //     MFMA operands through two exchange buffers (one per block parity), laid out as the consumers' 32x32x16
-//     A operands;
+//     A operands; after their MFMAs they request the dO rows and the row statistics of the next block;
 //   * consumers (waves 4-7): two row blocks behind, dV += P^T dO and -dK += (-dS)^T Q with dO^T / Q^T from LDS
-//     transpose reads (taken one interval early); they walk the schedule, issue the global -> LDS loads two
-//     row blocks ahead and leave a 16-byte header per stage;
+//     transpose reads (taken one interval early); they walk the schedule, request the Q rows two row blocks
+//     ahead and leave a header per stage (flags, rows, and where the block's dO rows and statistics are);
 //   * the main loop is unrolled over the four stages (immediate LDS offsets), one barrier per row block.
 #include <type_traits>
 #include "common.h"
@@ -44,7 +44,7 @@ constexpr int NDB = D / 128;                     // head-dim blocks per consumer
 constexpr int RB = 2 * D;
 constexpr int HT_BYTES = HB * RB;                // one Q or dO row block
 constexpr int STAT_OFF = 2 * HT_BYTES;           // lse2[16] | D[16]
-constexpr int HDR_OFF = STAT_OFF + 256;          // {flags, row0, nvalid, end marks so far}
+constexpr int HDR_OFF = STAT_OFF + 256;          // {flags, row0, nvalid, end marks so far}, {dO address, statistics address}
 constexpr int STAGE_BYTES = HDR_OFF + 64;
 constexpr int NBUF = 4;
 constexpr int XCH_OFF = NBUF * STAGE_BYTES;
