@@ -361,10 +361,11 @@ def test_prompt_groups_in_one_graph():
             check(want, "%s replay %d" % (name, rep))
 
 
-@pytest.mark.parametrize("d", [128, 256])
+@pytest.mark.parametrize("d", [128, 256, 512])
 def test_largest_token_stride(d):
-    """Inputs and gradient outputs as views whose token stride is the documented maximum (2^22 elements): the row
-    offsets the kernels form in 32 bits (24-bit multiplies in the tuned kernels) must still be exact."""
+    """Inputs (dO included) and gradient outputs as views whose token stride is the documented maximum (2^22 elements):
+    the row offsets the kernels form in 32 bits (24-bit multiplies, signed ones where the rows of a partial block are
+    clamped) must still be exact."""
     import torch
     from paper_2605_15422_amd import binding as B, runner
     print("case max_stride", d, flush=True)
@@ -380,12 +381,14 @@ def test_largest_token_stride(d):
         return big.as_strided((rows, heads, d), (TS, d, 1), row0 * TS + col0)
 
     cols = {"q": 0, "k": H * d, "v": (H + Hk) * d, "dq": (H + 2 * Hk) * d, "dk": (2 * H + 2 * Hk) * d,
-            "dv": (2 * H + 3 * Hk) * d}
+            "dv": (2 * H + 3 * Hk) * d, "do": (2 * H + 4 * Hk) * d}
     qc, kc, vc = view(0, P, cols["q"], H), view(0, P, cols["k"], Hk), view(0, P, cols["v"], Hk)
     qd, kd, vd = view(P, T, cols["q"], H), view(P, T, cols["k"], Hk), view(P, T, cols["v"], Hk)
-    for dst, src in ((qc, dg.q_c), (kc, dg.k_c), (vc, dg.v_c), (qd, dg.q_d), (kd, dg.k_d), (vd, dg.v_d)):
+    doc, dod = view(0, P, cols["do"], H), view(P, T, cols["do"], H)
+    for dst, src in ((qc, dg.q_c), (kc, dg.k_c), (vc, dg.v_c), (qd, dg.q_d), (kd, dg.k_d), (vd, dg.v_d), (doc, dg.do_c),
+                     (dod, dg.do_d)):
         dst.copy_(src)
-    dg2 = B.DeviceGroup(dg.shape_c, qc, kc, vc, qd, kd, vd, dg.do_c, dg.do_d, dg.cu_dev, dg.cu_host)
+    dg2 = B.DeviceGroup(dg.shape_c, qc, kc, vc, qd, kd, vd, doc, dod, dg.cu_dev, dg.cu_host)
     b1 = runner.alloc(dg)
     runner.layer_step(dg, b1)
     b2 = runner.alloc(dg)
