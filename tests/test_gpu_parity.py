@@ -64,6 +64,13 @@ EDGE = [
     ("d512_long", 2, 400, [200, 45], 4, 2, 512, 0),
     ("d512_p0", 2, 0, [130, 31], 2, 1, 512, 0),
     ("d512_empty", 3, 48, [0, 20, 0], 4, 2, 512, 0),
+    # schedules of one, two and three 16-row blocks per key tile (G = 1): the hand-over of the dO requests between the
+    # first blocks and the main loop, and its end marks
+    ("d512_one_block", 1, 16, [9], 1, 1, 512, 0),
+    ("d512_two_blocks", 1, 20, [27], 1, 1, 512, 0),
+    ("d512_three_blocks", 2, 5, [40, 3], 1, 1, 512, 0),
+    ("d256_one_block", 1, 33, [21], 1, 1, 256, 0),
+    ("d256_win_one_block", 1, 70, [30], 1, 1, 256, 8),
 ]
 
 
